@@ -1,0 +1,159 @@
+/*
+ * das.h -- C ABI of the MI355X (gfx950) batched speculative-verification library.
+ *
+ * The calls follow the paper's statement of one rollout round (Sec. 3; Fig. 3
+ * right; Sec. 4.1.2): a drafter proposes a multi-token chain per sequence, the
+ * target model verifies all of them in parallel in one batched pass, and the
+ * accepted tokens advance generation -- with the guarantee (abstract, Sec. 5.1,
+ * Sec. 6) that the emitted tokens are those that decoding without speculation
+ * would have produced (greedy: token-identical; sampling: same distribution,
+ * via the speculative-sampling rejection rule the paper cites in Sec. 2).
+ *
+ * Conventions
+ *  - Every pointer argument is HOST memory owned by the caller unless a comment
+ *    says otherwise; the library copies what it needs before returning and has
+ *    written every output and synchronised its stream when a call returns.
+ *  - Every call returns DAS_OK (0) or a negative DAS_ERR_* code.  All argument
+ *    and state validation happens before any state change or kernel launch: a
+ *    failed call leaves KV contents, page tables and sequence state untouched.
+ *    No exception or abort crosses this boundary.
+ *  - A sequence is (ctx_len committed KV positions, one pending token whose KV
+ *    is not yet written).  das_verify_step scores the rows
+ *    [pending, draft_1 .. draft_k] at positions ctx_len .. ctx_len+k and leaves
+ *    the sequence SPECULATIVE; exactly one of das_kv_commit / das_kv_rollback
+ *    must follow before the next verify step.
+ *  - KV lives in pages of 16 tokens, bf16.  Page ids are handed out from a
+ *    stack whose first pop is page 0, in batch order then ascending position;
+ *    pages are returned in batch order, highest page position first.
+ *  - The library is not thread-safe per model: calls on one das_model must not
+ *    overlap.
+ */
+#ifndef DAS_H
+#define DAS_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DAS_OK            0
+#define DAS_ERR_INVALID  (-1)   /* bad argument (null, out of range, duplicate id, over a configured maximum) */
+#define DAS_ERR_STATE    (-2)   /* call not allowed in the sequence's state, or ctx_len mismatch */
+#define DAS_ERR_NOMEM    (-3)   /* out of KV pages, sequence slots, or device/host memory */
+#define DAS_ERR_DEVICE   (-4)   /* a HIP call failed; das_last_device_error() has the text */
+
+typedef struct das_model das_model;   /* opaque: device weights, KV pool, page tables, sequence table, stream */
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim /* 64 or 128 */, d_ffn, vocab;
+    float   rope_theta, rms_eps;
+    int32_t page_size;      /* must be 16 */
+    int32_t max_seqs;       /* sequence slots */
+    int32_t max_ctx;        /* most positions one sequence may hold, drafts included */
+    int32_t max_rows;       /* most rows (sum of 1+k_i) in one verify step; also the prefill pass size */
+    int32_t max_draft;      /* largest k_i; (1+max_draft) * n_q_heads/n_kv_heads must be <= 256 */
+    int64_t num_pages;      /* KV pool size in pages */
+} das_config;
+
+/* Sampling inputs for stochastic rollouts.  One uniform in [0,1) per ROW of the
+ * step (row-aligned with [pending, drafts..] of every sequence, batch order):
+ * u_accept[row j] decides draft j+1, u_sample[row j] draws the token emitted
+ * after row j.  NULL das_sampling* means greedy decoding. */
+typedef struct {
+    float temperature;          /* > 0 */
+    const float *u_accept;
+    const float *u_sample;
+} das_sampling;
+
+/* Random-init (or any) weights.  `weights_bf16` is the canonical blob, every
+ * matrix [out_features][in_features] row-major, bf16 bit patterns:
+ *   embed[V][d]; per layer g1[d] Wq[Hq*D][d] Wk[Hkv*D][d] Wv[Hkv*D][d] Wo[d][Hq*D]
+ *   g2[d] Wg[F][d] Wu[F][d] Wd[d][F]; then gf[d] Wlm[V][d].
+ * The library repacks it on the device.  `hip_stream` is a hipStream_t the
+ * library should run on, or NULL to create its own.  Allocates all device
+ * memory (weights, KV pool of num_pages, workspaces).  Cheap to call again:
+ * an RL loop reloads weights every iteration. */
+int das_model_load(const das_config *cfg, const uint16_t *weights_bf16, void *hip_stream, das_model **out);
+int das_model_free(das_model *m);
+
+/* Prefill n NEW sequences (ids must be unused).  tokens = concatenated prompts,
+ * lens[i] >= 1.  Writes KV for every prompt position and returns the first
+ * pending token of each sequence (greedy argmax, lowest index on ties; or, with
+ * sampling, an inverse-CDF draw from softmax(logits/T) using u_sample[i], one
+ * value per SEQUENCE; u_accept unused).  Sequences end COMMITTED with
+ * ctx_len = lens[i]. */
+int das_prefill(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *tokens, const int32_t *lens,
+                const das_sampling *sampling, int32_t *next_token);
+
+/* One batched verification pass (Sec. 3; Fig. 3 right).  seq_ids unique,
+ * COMMITTED; ctx_lens[i] is checked against the library's committed length
+ * (DAS_ERR_STATE on mismatch); draft_tokens = concatenated chains, draft_lens[i]
+ * = k_i in [0, max_draft].
+ * Greedy: g_j = argmax of row j's logits; accept_len = longest prefix with
+ * draft_j == g_{j-1}; next_token = g_{accept_len}.
+ * Sampling: for j = 0..k-1 accept draft_{j+1} iff u_accept[j]*Z_j < w_j(draft_{j+1})
+ * with w = exp(logit/T - max), Z = sum w; on the first rejection next_token is
+ * the inverse-CDF draw (ascending vocabulary order, u_sample[j]) from w with
+ * the rejected token's weight zeroed; if all accepted, a draw from row k.
+ * Leaves every sequence SPECULATIVE.  Nothing is committed. */
+int das_verify_step(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *ctx_lens,
+                    const int32_t *draft_tokens, const int32_t *draft_lens,
+                    const das_sampling *sampling, int32_t *accept_len, int32_t *next_token);
+
+/* Accepted tokens advance generation (Fig. 3 right): ctx_len += 1 + accept_lens[i]
+ * (0 <= accept_lens[i] <= k_i of the pending step), pending = next_tokens[i],
+ * pages past the new length are returned.  The caller normally passes the
+ * step's own outputs; a parity harness may pass another decision (the KV rows
+ * of the drafts depend only on the input tokens). */
+int das_kv_commit(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *accept_lens,
+                  const int32_t *next_tokens);
+/* Discard every row of the pending step; ctx_len and the pending token are unchanged. */
+int das_kv_rollback(das_model *m, int32_t n, const int32_t *seq_ids);
+/* Release sequences (any state) and their pages. */
+int das_seq_free(das_model *m, int32_t n, const int32_t *seq_ids);
+
+/* ---- state injection: contexts whose KV is an input rather than a prefill ---- */
+/* New COMMITTED sequence of ctx_len positions (KV contents unspecified until imported) and a pending token. */
+int das_seq_create(das_model *m, int32_t seq_id, int32_t ctx_len, int32_t pending_token);
+/* Copy K and V rows [first_pos, first_pos+n_pos) of one layer; k, v are bf16 [n_pos][n_kv_heads][head_dim]. */
+int das_kv_import(das_model *m, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos,
+                  const uint16_t *k, const uint16_t *v);
+int das_kv_export(das_model *m, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos,
+                  uint16_t *k, uint16_t *v);
+/* Fill positions [0, ctx_len) of every layer on the device with the keyed synthetic
+ * generator: element e of the [pos][kv_head][dim] tensor of (layer, which in {K=0,V=1}) is
+ * bf16(s * 2^-15), s = centred sum of the four 16-bit fields of
+ * mix(mix(mix(mix(seed ^ 0x4B5653594E544821) ^ seq_key) ^ (2*layer+which)) ^ e), mix = splitmix64 step. */
+int das_kv_synth(das_model *m, int32_t seq_id, uint64_t seed, uint64_t seq_key);
+
+/* ---- inspection (tests, parity harness, bench) ---- */
+/* Row count of the last forward pass that produced logits. */
+int das_debug_num_rows(das_model *m, int32_t *n_rows);
+/* fp32 logits of rows [first_row, first_row+n_rows) of the last pass; out[n_rows][vocab]. */
+int das_debug_logits(das_model *m, int32_t first_row, int32_t n_rows, float *out);
+/* Greedy token of every row of the last pass; out[n_rows_of_pass]. */
+int das_debug_row_argmax(das_model *m, int32_t *out);
+/* Sequence state: committed length, pending token, state (0 COMMITTED, 1 SPECULATIVE), page list.
+ * pages may be NULL; *n_pages receives the count (pages must hold that many when non-NULL). */
+int das_debug_seq(das_model *m, int32_t seq_id, int32_t *ctx_len, int32_t *pending, int32_t *state,
+                  int32_t *pages, int32_t *n_pages);
+int das_debug_free_pages(das_model *m, int64_t *n_free);
+/* Stand-alone run of the MFMA GEMM kernel the projections use: c[M][N] (fp32) = a[M][K] * w[N][K]^T,
+ * a and w row-major bf16, K a multiple of 8.  Needs no model. */
+int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c);
+
+/* ---- per-kernel timing with HIP events on the library's own stream ---- */
+#define DAS_NUM_KERNEL_CLASSES 16
+int das_profile_enable(das_model *m, int32_t on);          /* on: every launch is bracketed by events */
+int das_profile_reset(das_model *m);
+/* Accumulated device time (ms) and launch count of one kernel class since the last reset. */
+int das_profile_read(das_model *m, int32_t kernel_class, double *ms, int64_t *launches);
+const char *das_profile_name(int32_t kernel_class);        /* NULL past the last class */
+
+const char *das_strerror(int code);
+const char *das_last_device_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAS_H */

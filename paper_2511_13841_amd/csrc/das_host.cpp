@@ -1,0 +1,833 @@
+// Host side of the C ABI declared in include/das.h: model and KV-pool
+// ownership, sequence table, page allocator, argument validation, and the
+// orchestration of one forward pass (verify step or prefill pass) as a
+// sequence of HIP kernel launches on one stream.
+#include "das_internal.h"
+#include "../../include/das.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <unordered_map>
+#include <unordered_set>
+#include <vector>
+
+static thread_local std::string g_dev_err;
+
+#define HIPCHK(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) {                                                                   \
+            g_dev_err = std::string(#expr) + ": " + hipGetErrorString(e_);                        \
+            return DAS_ERR_DEVICE;                                                                \
+        }                                                                                         \
+    } while (0)
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+enum { SEQ_FREE = -1, SEQ_COMMITTED = 0, SEQ_SPECULATIVE = 1 };
+
+struct Seq {
+    int id = -1, state = SEQ_FREE, ctx = 0, pending = -1, spec_rows = 0;
+    std::vector<int> pages;
+};
+
+struct LayerW { bf16_t *g1, *wqkv, *wo, *g2, *wgu, *wd; };
+
+struct PassBlock { int slot, start, n; const int32_t *toks; int want; /* 0 none, 1 last row, 2 all rows */ };
+
+struct das_model {
+    das_config cfg;
+    DasDims dm;
+    hipStream_t st = nullptr;
+    bool own_stream = false;
+    int max_pages = 0, Mp = 0;
+    // weights
+    bf16_t *embed = nullptr, *gf = nullptr, *wlm = nullptr;
+    std::vector<LayerW> layers;
+    std::vector<void *> allocs;             // everything to hipFree
+    double *inv_freq = nullptr;
+    // KV pool: [layer][page][Hkv][16*D] for K and for V
+    bf16_t *kpool = nullptr, *vpool = nullptr;
+    size_t layer_elems = 0;
+    int *page_table = nullptr;
+    // workspaces
+    float *h = nullptr, *cs = nullptr, *logits = nullptr, *row_stats = nullptr;
+    bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
+    float *part_acc = nullptr, *part_ml = nullptr;
+    size_t part_rows_cap = 0;
+    int *d_g = nullptr, *d_accept = nullptr, *d_next = nullptr;
+    // staging
+    int *h_stage = nullptr, *d_stage = nullptr;
+    size_t stage_ints = 0;
+    int *h_out = nullptr;                   // pinned: g[max_rows], accept[max_seqs], next[max_seqs]
+    // tables
+    std::vector<Seq> slots;
+    std::vector<int> free_slots;
+    std::unordered_map<int, int> id2slot;
+    std::vector<int> free_pages;
+    std::vector<int> pending_upd;           // (index, page) pairs for the device page table
+    int last_rows = 0;
+    // profiling
+    bool prof = false;
+    struct Ev { int cls; hipEvent_t a, b; };
+    std::vector<Ev> ev_used;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;
+    double prof_ms[KC_COUNT] = {0};
+    long long prof_n[KC_COUNT] = {0};
+};
+
+static const char *kClassNames[KC_COUNT] = {
+    "meta", "embed", "rmsnorm", "gemm_qkv", "rope_kv_write", "attention", "attention_merge", "gemm_o",
+    "gemm_gateup_silu", "gemm_down", "gemm_lm_head", "argmax", "accept_greedy", "accept_sample", "kv_io"};
+
+// ------------------------------------------------------------------------------------------------ helpers
+
+template <typename T>
+static int dev_alloc(das_model *m, T **p, size_t count) {
+    void *q = nullptr;
+    hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
+    if (e != hipSuccess) { g_dev_err = std::string("hipMalloc: ") + hipGetErrorString(e); (void)hipGetLastError(); return DAS_ERR_NOMEM; }
+    m->allocs.push_back(q);
+    *p = reinterpret_cast<T *>(q);
+    return DAS_OK;
+}
+
+struct ProfScope {
+    das_model *m; int cls; hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(das_model *mm, int c) : m(mm), cls(c) {
+        if (!m->prof) return;
+        if (m->ev_pool.empty()) {
+            hipEvent_t x, y;
+            if (hipEventCreate(&x) != hipSuccess || hipEventCreate(&y) != hipSuccess) return;
+            m->ev_pool.push_back({x, y});
+        }
+        a = m->ev_pool.back().first; b = m->ev_pool.back().second;
+        m->ev_pool.pop_back();
+        (void)hipEventRecord(a, m->st);
+    }
+    ~ProfScope() {
+        if (!a) return;
+        (void)hipEventRecord(b, m->st);
+        m->ev_used.push_back({cls, a, b});
+    }
+};
+
+static void prof_collect(das_model *m) {          // call after the stream is synchronised
+    for (auto &e : m->ev_used) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) { m->prof_ms[e.cls] += ms; m->prof_n[e.cls] += 1; }
+        m->ev_pool.push_back({e.a, e.b});
+    }
+    m->ev_used.clear();
+}
+
+static int pages_for(int tokens) { return (tokens + DAS_PAGE - 1) / DAS_PAGE; }
+
+static void grow_pages(das_model *m, int slot, int tokens) {
+    Seq &s = m->slots[slot];
+    while ((int)s.pages.size() < pages_for(tokens)) {
+        int pg = m->free_pages.back();
+        m->free_pages.pop_back();
+        m->pending_upd.push_back(slot * m->max_pages + (int)s.pages.size());
+        m->pending_upd.push_back(pg);
+        s.pages.push_back(pg);
+    }
+}
+static void shrink_pages(das_model *m, int slot, int tokens) {
+    Seq &s = m->slots[slot];
+    while ((int)s.pages.size() > pages_for(tokens)) { m->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
+}
+
+static int ensure_partials(das_model *m, size_t rows) {
+    if (rows <= m->part_rows_cap) return DAS_OK;
+    HIPCHK(hipStreamSynchronize(m->st));
+    size_t cap = std::max(rows, m->part_rows_cap * 2);
+    if (m->part_acc) { (void)hipFree(m->part_acc); (void)hipFree(m->part_ml); m->part_acc = nullptr; m->part_ml = nullptr; m->part_rows_cap = 0; }
+    hipError_t e1 = hipMalloc((void **)&m->part_acc, cap * m->dm.Hkv * m->dm.D * sizeof(float));
+    hipError_t e2 = hipMalloc((void **)&m->part_ml, cap * m->dm.Hkv * 2 * sizeof(float));
+    if (e1 != hipSuccess || e2 != hipSuccess) {
+        g_dev_err = "hipMalloc(attention partials) failed"; (void)hipGetLastError();
+        if (e1 == hipSuccess) (void)hipFree(m->part_acc);
+        if (e2 == hipSuccess) (void)hipFree(m->part_ml);
+        m->part_acc = m->part_ml = nullptr;
+        return DAS_ERR_NOMEM;
+    }
+    m->part_rows_cap = cap;
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ one forward pass
+// Rows of all blocks go through the layer stack; logits (+ argmax) are produced for the
+// selected rows.  On return kernels are enqueued, nothing is synchronised.
+static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const float *u_accept, const float *u_sample,
+                    int n_u, PassMeta *pm_out, const float **d_ua, const float **d_us) {
+    const DasDims &dm = m->dm;
+    const int NB = (int)blocks.size();
+    int T = 0;
+    for (auto &b : blocks) T += b.n;
+    std::vector<int> items[3];
+    size_t prow = 0;
+    // ---- pack the metadata
+    int *p = m->h_stage;
+    int *tok = p; p += T;
+    int *row_pos = p; p += T;
+    int *row_b = p; p += T;
+    int *sel = p; p += T;
+    int *b_slot = p; p += NB;
+    int *b_start = p; p += NB;
+    int *b_n = p; p += NB;
+    int *b_row0 = p; p += NB;
+    int *b_prow = p; p += NB;
+    int *b_nchunk = p; p += NB;
+    int r = 0, n_sel = 0;
+    for (int b = 0; b < NB; ++b) {
+        const PassBlock &pb = blocks[b];
+        b_slot[b] = pb.slot; b_start[b] = pb.start; b_n[b] = pb.n; b_row0[b] = r;
+        const int R = dm.G * pb.n, nrb = (R + 15) / 16;
+        const int nchunk = (pb.start + pb.n + DAS_ATTN_CHUNK - 1) / DAS_ATTN_CHUNK;
+        b_prow[b] = (int)prow; b_nchunk[b] = nchunk;
+        prow += (size_t)nchunk * R;
+        const int cls = nrb <= 4 ? 0 : (nrb <= 8 ? 1 : 2);
+        for (int c = 0; c < nchunk; ++c) { items[cls].push_back(b); items[cls].push_back(c); }
+        for (int j = 0; j < pb.n; ++j, ++r) {
+            tok[r] = pb.toks[j]; row_pos[r] = pb.start + j; row_b[r] = b;
+            if (pb.want == 2 || (pb.want == 1 && j == pb.n - 1)) sel[n_sel++] = r;
+        }
+    }
+    if (prow > 0x7FFFFFFFull) return DAS_ERR_NOMEM;
+    int *item_ptr[3];
+    for (int c = 0; c < 3; ++c) { item_ptr[c] = p; std::copy(items[c].begin(), items[c].end(), p); p += items[c].size(); }
+    const int n_upd = (int)m->pending_upd.size() / 2;
+    int *upd = p; std::copy(m->pending_upd.begin(), m->pending_upd.end(), p); p += 2 * n_upd;
+    float *ua = reinterpret_cast<float *>(p);
+    if (u_accept) { std::memcpy(p, u_accept, sizeof(float) * n_u); p += n_u; }
+    float *us = reinterpret_cast<float *>(p);
+    if (u_sample) { std::memcpy(p, u_sample, sizeof(float) * n_u); p += n_u; }
+    const size_t used = (size_t)(p - m->h_stage);
+    if (used > m->stage_ints) return DAS_ERR_INVALID;
+    int rc = ensure_partials(m, prow);
+    if (rc != DAS_OK) return rc;
+
+    hipStream_t st = m->st;
+    auto dptr = [&](const void *hp) { return m->d_stage + (reinterpret_cast<const int *>(hp) - m->h_stage); };
+    PassMeta pm;
+    pm.T = T; pm.NB = NB;
+    pm.tok = dptr(tok); pm.row_pos = dptr(row_pos); pm.row_b = dptr(row_b); pm.sel = dptr(sel); pm.n_sel = n_sel;
+    pm.b_slot = dptr(b_slot); pm.b_start = dptr(b_start); pm.b_n = dptr(b_n); pm.b_row0 = dptr(b_row0);
+    pm.b_prow = dptr(b_prow); pm.b_nchunk = dptr(b_nchunk);
+    pm.page_table = m->page_table; pm.max_pages = m->max_pages;
+    {
+        ProfScope ps(m, KC_META);
+        HIPCHK(hipMemcpyAsync(m->d_stage, m->h_stage, used * sizeof(int), hipMemcpyHostToDevice, st));
+        launch_pt_update(m->page_table, dptr(upd), n_upd, st);
+        m->pending_upd.clear();
+        launch_rope_table(pm, m->inv_freq, m->cs, dm.D, st);
+    }
+    { ProfScope ps(m, KC_EMBED); launch_embed(pm, m->embed, m->h, dm.d, st); }
+    for (int l = 0; l < dm.L; ++l) {
+        const LayerW &w = m->layers[l];
+        bf16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
+        { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
+        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_BF16_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st); }
+        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->cs, kl, vl, dm, st); }
+        {
+            ProfScope ps(m, KC_ATTN);
+            for (int c = 0; c < 3; ++c)
+                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->qkv, kl, vl, m->part_acc, m->part_ml, dm, st);
+        }
+        { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_acc, m->part_ml, m->attn, dm, st); }
+        { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st); }
+        { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g2, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
+        { ProfScope ps(m, KC_GEMM_GATEUP); launch_gemm(EPI_SILU_FRAG, m->xn, w.wgu, m->act, T, 2 * dm.Fp, dm.d, dm.Fp, st); }
+        { ProfScope ps(m, KC_GEMM_DOWN); launch_gemm(EPI_RESID_F32, m->act, w.wd, m->h, T, dm.d, dm.Fp, dm.d, st); }
+    }
+    if (n_sel > 0) {
+        { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, m->gf, m->xsel, pm.sel, n_sel, dm.d, dm.rms_eps, st); }
+        { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st); }
+        { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
+    }
+    hipError_t le = hipGetLastError();
+    if (le != hipSuccess) { g_dev_err = std::string("kernel launch: ") + hipGetErrorString(le); return DAS_ERR_DEVICE; }
+    m->last_rows = n_sel;
+    *pm_out = pm;
+    if (d_ua) *d_ua = reinterpret_cast<const float *>(dptr(ua));
+    if (d_us) *d_us = reinterpret_cast<const float *>(dptr(us));
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ load / free
+
+static int check_config(const das_config *c) {
+    if (!c) return DAS_ERR_INVALID;
+    if (c->n_layers < 1 || c->d_model < 64 || c->d_model % 64 || c->n_q_heads < 1 || c->n_kv_heads < 1 ||
+        c->n_q_heads % c->n_kv_heads || (c->head_dim != 64 && c->head_dim != 128) || c->d_ffn < 8 || c->d_ffn % 8 ||
+        c->vocab < 2 || !(c->rope_theta > 0.f) || !(c->rms_eps > 0.f))
+        return DAS_ERR_INVALID;
+    if (c->page_size != DAS_PAGE || c->max_seqs < 1 || c->max_ctx < DAS_PAGE || c->max_rows < 1 || c->max_draft < 0 ||
+        c->num_pages < 1 || c->num_pages > 0x3FFFFFFF)
+        return DAS_ERR_INVALID;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if ((1 + c->max_draft) * G > 256 || 1 + c->max_draft > c->max_rows) return DAS_ERR_INVALID;
+    if ((int64_t)c->max_rows * c->vocab > (int64_t)1 << 40) return DAS_ERR_INVALID;
+    return DAS_OK;
+}
+
+extern "C" int das_model_free(das_model *m) {
+    if (!m) return DAS_ERR_INVALID;
+    (void)hipStreamSynchronize(m->st);
+    for (void *p : m->allocs) (void)hipFree(p);
+    if (m->part_acc) (void)hipFree(m->part_acc);
+    if (m->part_ml) (void)hipFree(m->part_ml);
+    if (m->h_stage) (void)hipHostFree(m->h_stage);
+    if (m->h_out) (void)hipHostFree(m->h_out);
+    for (auto &e : m->ev_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+    for (auto &e : m->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    if (m->own_stream && m->st) (void)hipStreamDestroy(m->st);
+    delete m;
+    return DAS_OK;
+}
+
+static int load_impl(das_model *m, const uint16_t *wb) {
+    const das_config &c = m->cfg;
+    DasDims &dm = m->dm;
+    dm.L = c.n_layers; dm.d = c.d_model; dm.Hq = c.n_q_heads; dm.Hkv = c.n_kv_heads; dm.D = c.head_dim;
+    dm.F = c.d_ffn; dm.V = c.vocab; dm.G = dm.Hq / dm.Hkv; dm.Fp = round_up(dm.F, 64);
+    dm.qkvN = (dm.Hq + 2 * dm.Hkv) * dm.D; dm.rope_theta = c.rope_theta; dm.rms_eps = c.rms_eps;
+    m->max_pages = pages_for(c.max_ctx);
+    m->Mp = round_up(c.max_rows, 256);
+    const int d = dm.d, qd = dm.Hq * dm.D, kd = dm.Hkv * dm.D, F = dm.F, Fp = dm.Fp, V = dm.V;
+    const size_t Mp = m->Mp;
+    int rc;
+#define A(ptr, count) if ((rc = dev_alloc(m, &(ptr), (count))) != DAS_OK) return rc
+    // ---- weights: upload tensor by tensor through one scratch buffer, repack on the device
+    const size_t big = std::max((size_t)V * d, std::max((size_t)F * d * 2, (size_t)qd * d + 2 * (size_t)kd * d));
+    bf16_t *tmp; A(tmp, big);
+    A(m->embed, (size_t)V * d);
+    A(m->gf, (size_t)d);
+    const int Vp = round_up(V, 256), qkvNp = round_up(dm.qkvN, 256), dp = round_up(d, 256), gup = round_up(2 * Fp, 256);
+    A(m->wlm, (size_t)Vp * d);
+    m->layers.resize(dm.L);
+    const uint16_t *src = wb;
+    HIPCHK(hipMemcpy(m->embed, src, (size_t)V * d * 2, hipMemcpyHostToDevice)); src += (size_t)V * d;
+    for (int l = 0; l < dm.L; ++l) {
+        LayerW &w = m->layers[l];
+        A(w.g1, (size_t)d); A(w.g2, (size_t)d);
+        A(w.wqkv, (size_t)qkvNp * d); A(w.wo, (size_t)dp * qd); A(w.wgu, (size_t)gup * d); A(w.wd, (size_t)dp * Fp);
+        HIPCHK(hipMemcpy(w.g1, src, (size_t)d * 2, hipMemcpyHostToDevice)); src += d;
+        // Wq, Wk, Wv are adjacent in the blob: one [qkvN][d] matrix
+        HIPCHK(hipMemcpy(tmp, src, (size_t)dm.qkvN * d * 2, hipMemcpyHostToDevice)); src += (size_t)dm.qkvN * d;
+        launch_pack_weight(tmp, w.wqkv, dm.qkvN, d, qkvNp, d, m->st);
+        HIPCHK(hipStreamSynchronize(m->st));
+        HIPCHK(hipMemcpy(tmp, src, (size_t)d * qd * 2, hipMemcpyHostToDevice)); src += (size_t)d * qd;
+        launch_pack_weight(tmp, w.wo, d, qd, dp, qd, m->st);
+        HIPCHK(hipStreamSynchronize(m->st));
+        HIPCHK(hipMemcpy(w.g2, src, (size_t)d * 2, hipMemcpyHostToDevice)); src += d;
+        HIPCHK(hipMemcpy(tmp, src, (size_t)2 * F * d * 2, hipMemcpyHostToDevice)); src += (size_t)2 * F * d;
+        HIPCHK(hipMemsetAsync(w.wgu, 0, (size_t)gup * d * 2, m->st));
+        launch_pack_gateup(tmp, tmp + (size_t)F * d, w.wgu, F, d, Fp, m->st);
+        HIPCHK(hipStreamSynchronize(m->st));
+        HIPCHK(hipMemcpy(tmp, src, (size_t)d * F * 2, hipMemcpyHostToDevice)); src += (size_t)d * F;
+        launch_pack_weight(tmp, w.wd, d, F, dp, Fp, m->st);
+        HIPCHK(hipStreamSynchronize(m->st));
+    }
+    HIPCHK(hipMemcpy(m->gf, src, (size_t)d * 2, hipMemcpyHostToDevice)); src += d;
+    HIPCHK(hipMemcpy(tmp, src, (size_t)V * d * 2, hipMemcpyHostToDevice));
+    launch_pack_weight(tmp, m->wlm, V, d, Vp, d, m->st);
+    HIPCHK(hipStreamSynchronize(m->st));
+    // ---- RoPE inverse frequencies theta^(-2i/D), fp64
+    {
+        std::vector<double> f(dm.D / 2);
+        for (int i = 0; i < dm.D / 2; ++i) f[i] = std::pow((double)c.rope_theta, -2.0 * i / dm.D);
+        A(m->inv_freq, f.size());
+        HIPCHK(hipMemcpy(m->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice));
+    }
+    // ---- KV pool (zeroed: every value ever read from it is finite), page table
+    m->layer_elems = (size_t)c.num_pages * dm.Hkv * DAS_PAGE * dm.D;
+    A(m->kpool, m->layer_elems * dm.L);
+    A(m->vpool, m->layer_elems * dm.L);
+    HIPCHK(hipMemsetAsync(m->kpool, 0, m->layer_elems * dm.L * 2, m->st));
+    HIPCHK(hipMemsetAsync(m->vpool, 0, m->layer_elems * dm.L * 2, m->st));
+    A(m->page_table, (size_t)c.max_seqs * m->max_pages);
+    HIPCHK(hipMemsetAsync(m->page_table, 0, (size_t)c.max_seqs * m->max_pages * sizeof(int), m->st));
+    // ---- workspaces (row counts padded to 256 so GEMM tiles may over-read)
+    A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
+    A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
+    A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs);
+    HIPCHK(hipMemsetAsync(m->xn, 0, Mp * d * 2, m->st));
+    HIPCHK(hipMemsetAsync(m->attn, 0, Mp * qd * 2, m->st));
+    HIPCHK(hipMemsetAsync(m->act, 0, Mp * Fp * 2, m->st));
+    HIPCHK(hipMemsetAsync(m->xsel, 0, Mp * d * 2, m->st));
+    // ---- staging
+    const size_t max_items = (size_t)c.max_seqs * (c.max_ctx / DAS_ATTN_CHUNK + 2);
+    m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)c.max_seqs + 2 * max_items +
+                    2 * ((size_t)c.max_rows / DAS_PAGE + 2 * (size_t)c.max_seqs + 2) + 64;
+    HIPCHK(hipHostMalloc((void **)&m->h_stage, m->stage_ints * sizeof(int), hipHostMallocDefault));
+    A(m->d_stage, m->stage_ints);
+    HIPCHK(hipHostMalloc((void **)&m->h_out, ((size_t)c.max_rows + 2 * (size_t)c.max_seqs) * sizeof(int), hipHostMallocDefault));
+    // ---- tables
+    m->slots.resize(c.max_seqs);
+    for (int i = c.max_seqs - 1; i >= 0; --i) m->free_slots.push_back(i);
+    m->free_pages.reserve((size_t)c.num_pages);
+    for (int64_t i = c.num_pages - 1; i >= 0; --i) m->free_pages.push_back((int)i);   // pop_back() -> page 0 first
+    HIPCHK(hipStreamSynchronize(m->st));
+    // the upload scratch is no longer needed
+    (void)hipFree(tmp);
+    m->allocs.erase(std::find(m->allocs.begin(), m->allocs.end(), (void *)tmp));
+#undef A
+    return DAS_OK;
+}
+
+extern "C" int das_model_load(const das_config *cfg, const uint16_t *weights_bf16, void *hip_stream, das_model **out) {
+    if (!out || !weights_bf16) return DAS_ERR_INVALID;
+    *out = nullptr;
+    int rc = check_config(cfg);
+    if (rc != DAS_OK) return rc;
+    int ndev = 0;
+    HIPCHK(hipGetDeviceCount(&ndev));
+    if (ndev < 1) { g_dev_err = "no HIP device"; return DAS_ERR_DEVICE; }
+    das_model *m = new das_model();
+    m->cfg = *cfg;
+    if (hip_stream) m->st = reinterpret_cast<hipStream_t>(hip_stream);
+    else {
+        hipError_t e = hipStreamCreate(&m->st);
+        if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); delete m; return DAS_ERR_DEVICE; }
+        m->own_stream = true;
+    }
+    rc = load_impl(m, weights_bf16);
+    if (rc != DAS_OK) { das_model_free(m); return rc; }
+    *out = m;
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ lookups / validation
+
+static int find_slot(das_model *m, int id) {
+    auto it = m->id2slot.find(id);
+    return it == m->id2slot.end() ? -1 : it->second;
+}
+static bool unique_ids(int n, const int32_t *ids) {
+    std::unordered_set<int> s;
+    for (int i = 0; i < n; ++i) if (!s.insert(ids[i]).second) return false;
+    return true;
+}
+static int new_seq(das_model *m, int id) {
+    int slot = m->free_slots.back();
+    m->free_slots.pop_back();
+    Seq &s = m->slots[slot];
+    s = Seq();
+    s.id = id; s.state = SEQ_COMMITTED;
+    m->id2slot[id] = slot;
+    return slot;
+}
+static void purge_pending(das_model *m, int slot) {
+    std::vector<int> keep;
+    for (size_t i = 0; i + 1 < m->pending_upd.size(); i += 2)
+        if (m->pending_upd[i] / m->max_pages != slot) { keep.push_back(m->pending_upd[i]); keep.push_back(m->pending_upd[i + 1]); }
+    m->pending_upd.swap(keep);
+}
+static void drop_seq(das_model *m, int slot) {
+    Seq &s = m->slots[slot];
+    purge_pending(m, slot);
+    shrink_pages(m, slot, 0);
+    m->id2slot.erase(s.id);
+    s = Seq();
+    m->free_slots.push_back(slot);
+}
+static int upload_page_row(das_model *m, int slot) {
+    Seq &s = m->slots[slot];
+    purge_pending(m, slot);      // queued single-entry updates of this row: the whole row is written now
+    HIPCHK(hipStreamSynchronize(m->st));
+    if (!s.pages.empty())
+        HIPCHK(hipMemcpy(m->page_table + (size_t)slot * m->max_pages, s.pages.data(), s.pages.size() * sizeof(int), hipMemcpyHostToDevice));
+    return DAS_OK;
+}
+
+static int check_sampling(const das_sampling *s) {
+    if (!s) return DAS_OK;
+    if (!(s->temperature > 0.f) || !s->u_sample) return DAS_ERR_INVALID;
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ prefill
+
+extern "C" int das_prefill(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *tokens, const int32_t *lens,
+                           const das_sampling *sampling, int32_t *next_token) {
+    if (!m || n < 0) return DAS_ERR_INVALID;
+    if (n == 0) return DAS_OK;
+    if (!seq_ids || !tokens || !lens || !next_token || check_sampling(sampling) != DAS_OK) return DAS_ERR_INVALID;
+    if (!unique_ids(n, seq_ids)) return DAS_ERR_INVALID;
+    int64_t need_pages = 0, tot = 0;
+    for (int i = 0; i < n; ++i) {
+        if (lens[i] < 1 || lens[i] > m->cfg.max_ctx) return DAS_ERR_INVALID;
+        if (find_slot(m, seq_ids[i]) >= 0) return DAS_ERR_STATE;
+        need_pages += pages_for(lens[i]);
+        tot += lens[i];
+    }
+    for (int64_t i = 0; i < tot; ++i) if (tokens[i] < 0 || tokens[i] >= m->dm.V) return DAS_ERR_INVALID;
+    if ((int)m->free_slots.size() < n || need_pages > (int64_t)m->free_pages.size()) return DAS_ERR_NOMEM;
+
+    std::vector<int> slot(n), done(n, 0);
+    std::vector<const int32_t *> base(n);
+    const int32_t *tp = tokens;
+    for (int i = 0; i < n; ++i) {
+        slot[i] = new_seq(m, seq_ids[i]);
+        grow_pages(m, slot[i], lens[i]);
+        base[i] = tp; tp += lens[i];
+    }
+    int rc = DAS_OK;
+    for (int i = 0; i < n && rc == DAS_OK; ++i) rc = upload_page_row(m, slot[i]);
+    const int per_seq = std::min(256 / m->dm.G, m->cfg.max_rows);
+    int first = 0;                                   // first unfinished sequence
+    while (rc == DAS_OK && first < n) {
+        std::vector<PassBlock> blocks;
+        std::vector<int> who;
+        int T = 0;
+        for (int i = first; i < n && T < m->cfg.max_rows && (int)blocks.size() < m->cfg.max_seqs; ++i) {
+            if (done[i] >= lens[i]) continue;
+            int rows = std::min(std::min(lens[i] - done[i], per_seq), m->cfg.max_rows - T);
+            if (rows <= 0) break;
+            blocks.push_back({slot[i], done[i], rows, base[i] + done[i], (done[i] + rows == lens[i]) ? 1 : 0});
+            who.push_back(i);
+            T += rows;
+        }
+        PassMeta pm;
+        const float *d_ua = nullptr, *d_us = nullptr;
+        std::vector<float> us;
+        int n_fin = 0;
+        for (auto &b : blocks) n_fin += b.want ? 1 : 0;
+        if (sampling && n_fin) for (size_t bi = 0; bi < blocks.size(); ++bi) if (blocks[bi].want) us.push_back(sampling->u_sample[who[bi]]);
+        rc = run_pass(m, blocks, nullptr, us.empty() ? nullptr : us.data(), (int)us.size(), &pm, &d_ua, &d_us);
+        if (rc != DAS_OK) break;
+        if (n_fin) {
+            if (sampling) {
+                ProfScope ps(m, KC_SAMPLE);
+                launch_row_stats(m->logits, n_fin, m->dm.V, 1.f / sampling->temperature, m->row_stats, m->st);
+                launch_sample(m->logits, m->dm.V, pm.tok, pm.b_row0, pm.b_n, n_fin, 1.f / sampling->temperature, nullptr, d_us, 1,
+                              m->row_stats, m->d_accept, m->d_next, m->st);
+                if (hipMemcpyAsync(m->h_out, m->d_next, n_fin * sizeof(int), hipMemcpyDeviceToHost, m->st) != hipSuccess) rc = DAS_ERR_DEVICE;
+            } else {
+                if (hipMemcpyAsync(m->h_out, m->d_g, n_fin * sizeof(int), hipMemcpyDeviceToHost, m->st) != hipSuccess) rc = DAS_ERR_DEVICE;
+            }
+        }
+        if (hipStreamSynchronize(m->st) != hipSuccess) { g_dev_err = "stream synchronize failed in prefill"; rc = DAS_ERR_DEVICE; }
+        prof_collect(m);
+        if (rc != DAS_OK) break;
+        int f = 0;
+        for (size_t bi = 0; bi < blocks.size(); ++bi) {
+            int i = who[bi];
+            done[i] += blocks[bi].n;
+            if (blocks[bi].want) next_token[i] = m->h_out[f++];
+        }
+        while (first < n && done[first] >= lens[first]) ++first;
+    }
+    if (rc != DAS_OK) {                              // undo: the sequences never existed
+        for (int i = 0; i < n; ++i) drop_seq(m, slot[i]);
+        return rc;
+    }
+    for (int i = 0; i < n; ++i) {
+        Seq &s = m->slots[slot[i]];
+        s.ctx = lens[i]; s.pending = next_token[i]; s.state = SEQ_COMMITTED; s.spec_rows = 0;
+    }
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ verify
+
+extern "C" int das_verify_step(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *ctx_lens,
+                               const int32_t *draft_tokens, const int32_t *draft_lens, const das_sampling *sampling,
+                               int32_t *accept_len, int32_t *next_token) {
+    if (!m || n < 0) return DAS_ERR_INVALID;
+    if (n == 0) return DAS_OK;
+    if (!seq_ids || !ctx_lens || !draft_lens || !accept_len || !next_token || n > m->cfg.max_seqs) return DAS_ERR_INVALID;
+    if (check_sampling(sampling) != DAS_OK || (sampling && !sampling->u_accept)) return DAS_ERR_INVALID;
+    if (!unique_ids(n, seq_ids)) return DAS_ERR_INVALID;
+    int64_t T = 0, nd = 0, need_pages = 0;
+    for (int i = 0; i < n; ++i) {
+        if (draft_lens[i] < 0 || draft_lens[i] > m->cfg.max_draft) return DAS_ERR_INVALID;
+        T += 1 + draft_lens[i]; nd += draft_lens[i];
+    }
+    if (T > m->cfg.max_rows || (nd > 0 && !draft_tokens)) return DAS_ERR_INVALID;
+    for (int64_t i = 0; i < nd; ++i) if (draft_tokens[i] < 0 || draft_tokens[i] >= m->dm.V) return DAS_ERR_INVALID;
+    std::vector<int> slot(n);
+    for (int i = 0; i < n; ++i) {
+        slot[i] = find_slot(m, seq_ids[i]);
+        if (slot[i] < 0) return DAS_ERR_INVALID;
+        const Seq &s = m->slots[slot[i]];
+        if (s.state != SEQ_COMMITTED || s.ctx != ctx_lens[i]) return DAS_ERR_STATE;
+        if (s.ctx + 1 + draft_lens[i] > m->cfg.max_ctx) return DAS_ERR_INVALID;
+        need_pages += pages_for(s.ctx + 1 + draft_lens[i]) - (int64_t)s.pages.size();
+    }
+    if (need_pages > (int64_t)m->free_pages.size()) return DAS_ERR_NOMEM;
+
+    // ---- state changes start here
+    std::vector<int32_t> rows((size_t)T);
+    std::vector<PassBlock> blocks(n);
+    {
+        int r = 0; const int32_t *dp = draft_tokens;
+        for (int i = 0; i < n; ++i) {
+            Seq &s = m->slots[slot[i]];
+            grow_pages(m, slot[i], s.ctx + 1 + draft_lens[i]);
+            blocks[i] = {slot[i], s.ctx, 1 + draft_lens[i], rows.data() + r, 2};
+            rows[r++] = s.pending;
+            for (int j = 0; j < draft_lens[i]; ++j) rows[r++] = *dp++;
+        }
+    }
+    PassMeta pm;
+    const float *d_ua = nullptr, *d_us = nullptr;
+    int rc = run_pass(m, blocks, sampling ? sampling->u_accept : nullptr, sampling ? sampling->u_sample : nullptr, (int)T,
+                      &pm, &d_ua, &d_us);
+    if (rc == DAS_OK) {
+        if (sampling) {
+            ProfScope ps(m, KC_SAMPLE);
+            launch_row_stats(m->logits, (int)T, m->dm.V, 1.f / sampling->temperature, m->row_stats, m->st);
+            launch_sample(m->logits, m->dm.V, pm.tok, pm.b_row0, pm.b_n, n, 1.f / sampling->temperature, d_ua, d_us, 0,
+                          m->row_stats, m->d_accept, m->d_next, m->st);
+        } else {
+            ProfScope ps(m, KC_ACCEPT);
+            launch_accept_greedy(m->d_g, pm.b_row0, pm.b_n, pm.tok, n, m->d_accept, m->d_next, m->st);
+        }
+        if (hipMemcpyAsync(m->h_out, m->d_accept, n * sizeof(int), hipMemcpyDeviceToHost, m->st) != hipSuccess ||
+            hipMemcpyAsync(m->h_out + n, m->d_next, n * sizeof(int), hipMemcpyDeviceToHost, m->st) != hipSuccess)
+            rc = DAS_ERR_DEVICE;
+    }
+    if (hipStreamSynchronize(m->st) != hipSuccess) { g_dev_err = "stream synchronize failed in verify"; rc = DAS_ERR_DEVICE; }
+    prof_collect(m);
+    if (rc != DAS_OK) {                              // give the freshly taken pages back
+        for (int i = 0; i < n; ++i) shrink_pages(m, slot[i], m->slots[slot[i]].ctx);
+        return rc;
+    }
+    for (int i = 0; i < n; ++i) {
+        accept_len[i] = m->h_out[i];
+        next_token[i] = m->h_out[n + i];
+        Seq &s = m->slots[slot[i]];
+        s.state = SEQ_SPECULATIVE; s.spec_rows = 1 + draft_lens[i];
+    }
+    return DAS_OK;
+}
+
+extern "C" int das_kv_commit(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *accept_lens,
+                             const int32_t *next_tokens) {
+    if (!m || n < 0) return DAS_ERR_INVALID;
+    if (n == 0) return DAS_OK;
+    if (!seq_ids || !accept_lens || !next_tokens || !unique_ids(n, seq_ids)) return DAS_ERR_INVALID;
+    std::vector<int> slot(n);
+    for (int i = 0; i < n; ++i) {
+        slot[i] = find_slot(m, seq_ids[i]);
+        if (slot[i] < 0) return DAS_ERR_INVALID;
+        const Seq &s = m->slots[slot[i]];
+        if (s.state != SEQ_SPECULATIVE) return DAS_ERR_STATE;
+        if (accept_lens[i] < 0 || accept_lens[i] > s.spec_rows - 1 || next_tokens[i] < 0 || next_tokens[i] >= m->dm.V)
+            return DAS_ERR_INVALID;
+    }
+    for (int i = 0; i < n; ++i) {
+        Seq &s = m->slots[slot[i]];
+        s.ctx += 1 + accept_lens[i];
+        s.pending = next_tokens[i];
+        s.state = SEQ_COMMITTED; s.spec_rows = 0;
+        shrink_pages(m, slot[i], s.ctx);
+    }
+    return DAS_OK;
+}
+
+extern "C" int das_kv_rollback(das_model *m, int32_t n, const int32_t *seq_ids) {
+    if (!m || n < 0) return DAS_ERR_INVALID;
+    if (n == 0) return DAS_OK;
+    if (!seq_ids || !unique_ids(n, seq_ids)) return DAS_ERR_INVALID;
+    std::vector<int> slot(n);
+    for (int i = 0; i < n; ++i) {
+        slot[i] = find_slot(m, seq_ids[i]);
+        if (slot[i] < 0) return DAS_ERR_INVALID;
+        if (m->slots[slot[i]].state != SEQ_SPECULATIVE) return DAS_ERR_STATE;
+    }
+    for (int i = 0; i < n; ++i) {
+        Seq &s = m->slots[slot[i]];
+        s.state = SEQ_COMMITTED; s.spec_rows = 0;
+        shrink_pages(m, slot[i], s.ctx);
+    }
+    return DAS_OK;
+}
+
+extern "C" int das_seq_free(das_model *m, int32_t n, const int32_t *seq_ids) {
+    if (!m || n < 0) return DAS_ERR_INVALID;
+    if (n == 0) return DAS_OK;
+    if (!seq_ids || !unique_ids(n, seq_ids)) return DAS_ERR_INVALID;
+    for (int i = 0; i < n; ++i) if (find_slot(m, seq_ids[i]) < 0) return DAS_ERR_INVALID;
+    for (int i = 0; i < n; ++i) {
+        drop_seq(m, find_slot(m, seq_ids[i]));
+    }
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ state injection
+
+extern "C" int das_seq_create(das_model *m, int32_t seq_id, int32_t ctx_len, int32_t pending_token) {
+    if (!m || ctx_len < 0 || ctx_len >= m->cfg.max_ctx || pending_token < 0 || pending_token >= m->dm.V) return DAS_ERR_INVALID;
+    if (find_slot(m, seq_id) >= 0) return DAS_ERR_STATE;
+    if (m->free_slots.empty() || pages_for(ctx_len) > (int)m->free_pages.size()) return DAS_ERR_NOMEM;
+    int slot = new_seq(m, seq_id);
+    grow_pages(m, slot, ctx_len);
+    Seq &s = m->slots[slot];
+    s.ctx = ctx_len; s.pending = pending_token;
+    int rc = upload_page_row(m, slot);
+    if (rc != DAS_OK) drop_seq(m, slot);
+    return rc;
+}
+
+static int kv_io(das_model *m, int mode, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos, uint16_t *k, uint16_t *v) {
+    if (!m || !k || !v || layer < 0 || layer >= m->dm.L || first_pos < 0 || n_pos < 0) return DAS_ERR_INVALID;
+    int slot = find_slot(m, seq_id);
+    if (slot < 0) return DAS_ERR_INVALID;
+    Seq &s = m->slots[slot];
+    if (first_pos + n_pos > (int)s.pages.size() * DAS_PAGE) return DAS_ERR_INVALID;
+    if (n_pos == 0) return DAS_OK;
+    const size_t cnt = (size_t)n_pos * m->dm.Hkv * m->dm.D;
+    bf16_t *dk = nullptr, *dv = nullptr;
+    HIPCHK(hipStreamSynchronize(m->st));
+    if (hipMalloc((void **)&dk, cnt * 2) != hipSuccess) { (void)hipGetLastError(); return DAS_ERR_NOMEM; }
+    if (hipMalloc((void **)&dv, cnt * 2) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(dk); return DAS_ERR_NOMEM; }
+    int rc = DAS_OK;
+    bf16_t *kl = m->kpool + (size_t)layer * m->layer_elems, *vl = m->vpool + (size_t)layer * m->layer_elems;
+    const int *prow = m->page_table + (size_t)slot * m->max_pages;
+    auto fail = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
+    do {
+        if (mode == 0) {
+            if (fail(hipMemcpy(dk, k, cnt * 2, hipMemcpyHostToDevice))) break;
+            if (fail(hipMemcpy(dv, v, cnt * 2, hipMemcpyHostToDevice))) break;
+        }
+        { ProfScope ps(m, KC_KVIO); launch_kv_io(mode, prow, first_pos, n_pos, kl, vl, dk, dv, m->dm.Hkv, m->dm.D, m->st); }
+        if (fail(hipStreamSynchronize(m->st))) break;
+        if (mode == 1) {
+            if (fail(hipMemcpy(k, dk, cnt * 2, hipMemcpyDeviceToHost))) break;
+            if (fail(hipMemcpy(v, dv, cnt * 2, hipMemcpyDeviceToHost))) break;
+        }
+    } while (0);
+    prof_collect(m);
+    (void)hipFree(dk); (void)hipFree(dv);
+    return rc;
+}
+
+extern "C" int das_kv_import(das_model *m, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos,
+                             const uint16_t *k, const uint16_t *v) {
+    return kv_io(m, 0, seq_id, layer, first_pos, n_pos, const_cast<uint16_t *>(k), const_cast<uint16_t *>(v));
+}
+extern "C" int das_kv_export(das_model *m, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos,
+                             uint16_t *k, uint16_t *v) {
+    return kv_io(m, 1, seq_id, layer, first_pos, n_pos, k, v);
+}
+
+extern "C" int das_kv_synth(das_model *m, int32_t seq_id, uint64_t seed, uint64_t seq_key) {
+    if (!m) return DAS_ERR_INVALID;
+    int slot = find_slot(m, seq_id);
+    if (slot < 0) return DAS_ERR_INVALID;
+    Seq &s = m->slots[slot];
+    if (s.state != SEQ_COMMITTED) return DAS_ERR_STATE;
+    const int *prow = m->page_table + (size_t)slot * m->max_pages;
+    {
+        ProfScope ps(m, KC_KVIO);
+        for (int l = 0; l < m->dm.L; ++l)
+            launch_kv_synth(prow, s.ctx, m->kpool + (size_t)l * m->layer_elems, m->vpool + (size_t)l * m->layer_elems,
+                            m->dm.Hkv, m->dm.D, seed, seq_key, l, m->st);
+    }
+    HIPCHK(hipStreamSynchronize(m->st));
+    prof_collect(m);
+    return DAS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ inspection
+
+extern "C" int das_debug_num_rows(das_model *m, int32_t *n_rows) {
+    if (!m || !n_rows) return DAS_ERR_INVALID;
+    *n_rows = m->last_rows;
+    return DAS_OK;
+}
+extern "C" int das_debug_logits(das_model *m, int32_t first_row, int32_t n_rows, float *out) {
+    if (!m || !out || first_row < 0 || n_rows < 0 || first_row + n_rows > m->last_rows) return DAS_ERR_INVALID;
+    if (n_rows == 0) return DAS_OK;
+    HIPCHK(hipStreamSynchronize(m->st));
+    HIPCHK(hipMemcpy(out, m->logits + (size_t)first_row * m->dm.V, (size_t)n_rows * m->dm.V * sizeof(float), hipMemcpyDeviceToHost));
+    return DAS_OK;
+}
+extern "C" int das_debug_row_argmax(das_model *m, int32_t *out) {
+    if (!m || !out) return DAS_ERR_INVALID;
+    if (m->last_rows == 0) return DAS_OK;
+    HIPCHK(hipStreamSynchronize(m->st));
+    HIPCHK(hipMemcpy(out, m->d_g, (size_t)m->last_rows * sizeof(int), hipMemcpyDeviceToHost));
+    return DAS_OK;
+}
+extern "C" int das_debug_seq(das_model *m, int32_t seq_id, int32_t *ctx_len, int32_t *pending, int32_t *state,
+                             int32_t *pages, int32_t *n_pages) {
+    if (!m) return DAS_ERR_INVALID;
+    int slot = find_slot(m, seq_id);
+    if (slot < 0) return DAS_ERR_INVALID;
+    const Seq &s = m->slots[slot];
+    if (ctx_len) *ctx_len = s.ctx;
+    if (pending) *pending = s.pending;
+    if (state) *state = s.state;
+    if (n_pages) *n_pages = (int)s.pages.size();
+    if (pages) std::copy(s.pages.begin(), s.pages.end(), pages);
+    return DAS_OK;
+}
+extern "C" int das_debug_free_pages(das_model *m, int64_t *n_free) {
+    if (!m || !n_free) return DAS_ERR_INVALID;
+    *n_free = (int64_t)m->free_pages.size();
+    return DAS_OK;
+}
+
+// Stand-alone check of the MFMA GEMM: C[M][N] = A[M][K] * W[N][K]^T from row-major bf16 host inputs.
+extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c) {
+    if (M < 1 || N < 1 || K < 8 || (K % 8) || !a || !w || !c) return DAS_ERR_INVALID;
+    const int Mp = round_up(M, 256), Np = round_up(N, 256), Kp = round_up(K, 64);
+    bf16_t *da = nullptr, *dw = nullptr, *pa = nullptr, *pw = nullptr;
+    float *dc = nullptr;
+    int rc = DAS_OK;
+    auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
+    do {
+        if (bad(hipMalloc((void **)&da, (size_t)M * K * 2)) || bad(hipMalloc((void **)&dw, (size_t)N * K * 2)) ||
+            bad(hipMalloc((void **)&pa, (size_t)Mp * Kp * 2)) || bad(hipMalloc((void **)&pw, (size_t)Np * Kp * 2)) ||
+            bad(hipMalloc((void **)&dc, (size_t)M * N * 4))) break;
+        if (bad(hipMemcpy(da, a, (size_t)M * K * 2, hipMemcpyHostToDevice)) || bad(hipMemcpy(dw, w, (size_t)N * K * 2, hipMemcpyHostToDevice))) break;
+        launch_pack_weight(da, pa, M, K, Mp, Kp, nullptr);
+        launch_pack_weight(dw, pw, N, K, Np, Kp, nullptr);
+        launch_gemm(EPI_F32_ROWMAJOR, pa, pw, dc, M, N, Kp, N, nullptr);
+        if (bad(hipDeviceSynchronize())) break;
+        if (bad(hipMemcpy(c, dc, (size_t)M * N * 4, hipMemcpyDeviceToHost))) break;
+    } while (0);
+    (void)hipFree(da); (void)hipFree(dw); (void)hipFree(pa); (void)hipFree(pw); (void)hipFree(dc);
+    return rc;
+}
+
+// ------------------------------------------------------------------------------------------------ profiling / errors
+
+extern "C" int das_profile_enable(das_model *m, int32_t on) {
+    if (!m) return DAS_ERR_INVALID;
+    m->prof = on != 0;
+    return DAS_OK;
+}
+extern "C" int das_profile_reset(das_model *m) {
+    if (!m) return DAS_ERR_INVALID;
+    for (int i = 0; i < KC_COUNT; ++i) { m->prof_ms[i] = 0; m->prof_n[i] = 0; }
+    return DAS_OK;
+}
+extern "C" int das_profile_read(das_model *m, int32_t kernel_class, double *ms, int64_t *launches) {
+    if (!m || kernel_class < 0 || kernel_class >= KC_COUNT) return DAS_ERR_INVALID;
+    if (ms) *ms = m->prof_ms[kernel_class];
+    if (launches) *launches = m->prof_n[kernel_class];
+    return DAS_OK;
+}
+extern "C" const char *das_profile_name(int32_t kernel_class) {
+    return (kernel_class >= 0 && kernel_class < KC_COUNT) ? kClassNames[kernel_class] : nullptr;
+}
+extern "C" const char *das_strerror(int code) {
+    switch (code) {
+    case DAS_OK: return "ok";
+    case DAS_ERR_INVALID: return "invalid argument";
+    case DAS_ERR_STATE: return "call not allowed in this sequence state";
+    case DAS_ERR_NOMEM: return "out of pages, sequence slots or memory";
+    case DAS_ERR_DEVICE: return "HIP call failed";
+    default: return "unknown error";
+    }
+}
+extern "C" const char *das_last_device_error(void) { return g_dev_err.c_str(); }

@@ -1,0 +1,103 @@
+// Internal declarations shared by the host orchestration and the HIP kernels.
+//
+// Data layout in HBM (gfx950, wave64, MFMA):
+//  * GEMM operands, weights AND activations, are stored in "MFMA fragment
+//    order" for v_mfma_f32_32x32x16_bf16: a matrix X[R][K] (K contiguous in the
+//    logical view) is cut into fragments of 32 rows x 16 k; fragment
+//    (rb, ks) is 1 KiB = 64 lanes x 8 bf16, lane l holding row rb*32 + l%32,
+//    k = ks*16 + 8*(l/32) .. +7.  Fragments of one row block are contiguous
+//    in ks.  A wave fetches an operand with one fully coalesced 16-byte load
+//    per lane and no shuffling; tiles copy to LDS linearly and are read back
+//    with conflict-free ds_read_b128.
+//  * The KV cache is paged (16 tokens).  A K page of one KV head is stored as
+//    the A operand of v_mfma_f32_16x16x32_bf16 (16 tokens x 32 dims per
+//    fragment, D/32 fragments); a V page as [D/16 dim blocks][4 token
+//    groups][16 dims][4 tokens] so that a lane's 8-byte load from each of two
+//    pages forms the A operand of the P*V product over a 32-token tile.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;   // raw bf16 bit pattern in memory
+
+#define DAS_PAGE 16
+#define DAS_ATTN_CHUNK 1024          // tokens per split-KV work item (absolute-position aligned)
+#define DAS_ATTN_TILE 32             // tokens per inner tile = 2 pages
+
+enum DasKernelClass {
+    KC_META = 0, KC_EMBED, KC_RMSNORM, KC_GEMM_QKV, KC_ROPE_KV, KC_ATTN, KC_ATTN_MERGE, KC_GEMM_O,
+    KC_GEMM_GATEUP, KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_ARGMAX, KC_ACCEPT, KC_SAMPLE, KC_KVIO, KC_COUNT
+};
+
+// element offset of X[row][k] inside a fragment-ordered matrix with K columns (K % 16 == 0)
+__host__ __device__ inline size_t frag_off(int row, int k, int K) {
+    return ((size_t)(row >> 5) * (size_t)(K >> 4) + (size_t)(k >> 4)) * 512
+         + (size_t)((((k >> 3) & 1) << 5) + (row & 31)) * 8 + (size_t)(k & 7);
+}
+
+// element offset of (token t in page, dim d) inside one (page, head) K block of head dim D
+__host__ __device__ inline int kpage_off(int t, int d) {
+    return (((d >> 5) * 64) + (((d & 31) >> 3) * 16 + t)) * 8 + (d & 7);
+}
+// element offset of (token t in page, dim d) inside one (page, head) V block
+__host__ __device__ inline int vpage_off(int t, int d) {
+    return ((((d >> 4) * 4 + (t >> 2)) * 16) + (d & 15)) * 4 + (t & 3);
+}
+
+struct DasDims {
+    int L, d, Hq, Hkv, D, F, V, G;
+    int Fp;        // d_ffn padded to a multiple of 64 (zero weights)
+    int qkvN;      // (Hq + 2 Hkv) * D
+    float rope_theta, rms_eps;
+};
+
+// Per-pass metadata, all device pointers into one staging block.
+struct PassMeta {
+    int T;                 // rows in this pass
+    int NB;                // sequences (blocks) in this pass
+    const int *tok;        // [T]
+    const int *row_pos;    // [T] absolute position
+    const int *row_b;      // [T] block index
+    const int *b_slot;     // [NB] page-table row
+    const int *b_start;    // [NB] first position of the block (= committed length)
+    const int *b_n;        // [NB] rows of the block
+    const int *b_row0;     // [NB] first row of the block
+    const int *b_prow;     // [NB] base row in the split-KV partial buffers
+    const int *b_nchunk;   // [NB] split-KV chunks
+    const int *sel;        // [n_sel] rows that get logits
+    int n_sel;
+    const int *page_table; // [max_seqs][max_pages]
+    int max_pages;
+};
+
+enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3 };
+
+// ---- launchers (each enqueues on `st`; none synchronises) ----
+void launch_pack_weight(const bf16_t *src, bf16_t *dst, int N, int K, int Np, int Kp, hipStream_t st);
+void launch_pack_gateup(const bf16_t *wg, const bf16_t *wu, bf16_t *dst, int F, int K, int Fp, hipStream_t st);
+void launch_pt_update(int *page_table, const int *upd, int n_upd, hipStream_t st);
+void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStream_t st);
+// y (fragment order, K = d) = rmsnorm(h[row]) for row = sel ? sel[i] : i, i < n
+void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st);
+void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, int D, hipStream_t st);
+void launch_rope_kv(const PassMeta &pm, bf16_t *qkv, const float *cs, bf16_t *kpool_layer, bf16_t *vpool_layer,
+                    const DasDims &dm, hipStream_t st);
+// C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
+void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st);
+// split-KV partial attention for the items of one row-block class, then the merge
+void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *qkv,
+                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, float *part_acc, float *part_ml,
+                 const DasDims &dm, hipStream_t st);
+void launch_attn_merge(const PassMeta &pm, const float *part_acc, const float *part_ml, bf16_t *out_frag,
+                       const DasDims &dm, hipStream_t st);
+void launch_argmax(const float *logits, int n_rows, int V, int *out, hipStream_t st);
+void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const int *tok, int NB,
+                          int *accept_len, int *next_token, hipStream_t st);
+void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, float *stats, hipStream_t st);
+void launch_sample(const float *logits, int V, const int *tok, const int *b_row0, const int *b_n, int NB,
+                   float inv_temp, const float *u_accept, const float *u_sample, int prefill_mode,
+                   float *row_stats, int *accept_len, int *next_token, hipStream_t st);
+void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_t *kpool_layer, bf16_t *vpool_layer,
+                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, hipStream_t st);
+void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D,
+                     uint64_t seed, uint64_t seq_key, int layer, hipStream_t st);

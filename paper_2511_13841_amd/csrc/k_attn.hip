@@ -1,0 +1,252 @@
+// Ragged causal GQA attention over the paged bf16 KV cache (split-KV).
+//
+// One workgroup = one (sequence, KV head, 1024-token chunk).  All G*(1+k_i)
+// query rows that share the KV head are served by ONE pass over the chunk's
+// KV: arithmetic per KV byte is G*(1+k) <= 231 flop/B, below the machine's
+// ridge, so the kernel is built around streaming pages at HBM rate:
+//   * pages are stored in MFMA operand order, so a 32-token tile (2 pages of K
+//     and of V) is four contiguous runs copied to LDS with coalesced 16-byte
+//     loads, double buffered, and read back lane-linearly (no bank conflicts);
+//   * S^T = K Q^T with v_mfma_f32_16x16x32_bf16 puts 8 tokens of one query row
+//     in each lane, so the row max needs two cross-lane steps and the
+//     probabilities are already laid out as the B operand of O^T += V^T P^T;
+//   * chunks start at absolute multiples of 1024 tokens and each chunk is
+//     reduced from scratch, then chunks are merged in ascending order: a row's
+//     result does not depend on the batch it is verified in (speculative
+//     verification and one-token decoding give bit-identical rows).
+// Wave w owns query-row blocks (16 rows each) w*RBW .. w*RBW+RBW-1.
+#include "das_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int D, int RBW>
+__global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
+                                                           const bf16_t *__restrict__ qkv,
+                                                           const bf16_t *__restrict__ kpool,
+                                                           const bf16_t *__restrict__ vpool,
+                                                           float *__restrict__ part_acc, float *__restrict__ part_ml,
+                                                           int Hkv, int G, int qkvN, float scale_log2e) {
+    constexpr int KFR = D / 32;            // K fragments (1 KiB) per page
+    constexpr int VDB = D / 16;            // V dim blocks (512 B) per page
+    constexpr int PAGE_E = DAS_PAGE * D;   // elements of one (page, head) block
+    constexpr int PAGE_B = PAGE_E * 2;
+    constexpr int TILE_B = 4 * PAGE_B;     // K page0, K page1, V page0, V page1
+    constexpr int UNITS_PER_SEG = PAGE_B / 16;
+    constexpr int NLOAD = (TILE_B / 16) / 256;
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int b = items[2 * blockIdx.x], chunk = items[2 * blockIdx.x + 1];
+    const int kvh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ctx = pm.b_start[b], n = pm.b_n[b], row0 = pm.b_row0[b];
+    const int R = G * n;
+    const int tok_begin = chunk * DAS_ATTN_CHUNK;
+    const int tok_total = ctx + n;
+    const int tok_end = min(tok_begin + DAS_ATTN_CHUNK, tok_total);
+    const int ntiles = (tok_end - tok_begin + DAS_ATTN_TILE - 1) / DAS_ATTN_TILE;
+    const int npages = (tok_total + DAS_PAGE - 1) / DAS_PAGE;
+    const int *pt = pm.page_table + (size_t)pm.b_slot[b] * pm.max_pages;
+
+    // ---- query fragments (B operand: lane l = query row l%16, dims 8*(l/16)..+7 of each 32-dim step)
+    bf16x8 qf[RBW][KFR];
+    int lim[RBW];           // last KV position this lane's query row may see (-1: padding row)
+    bool any_active = false;
+#pragma unroll
+    for (int i = 0; i < RBW; ++i) {
+        const int rr = (wave * RBW + i) * 16 + (lane & 15);
+        const bool valid = rr < R;
+        const int j = valid ? rr / G : 0, g = valid ? rr % G : 0;
+        lim[i] = valid ? ctx + j : -1;
+        any_active |= ((wave * RBW + i) * 16 < R);
+        const bf16_t *src = qkv + (size_t)(row0 + j) * qkvN + (size_t)(kvh * G + g) * D + 8 * (lane >> 4);
+#pragma unroll
+        for (int ks = 0; ks < KFR; ++ks) {
+            uint4 v = valid ? *reinterpret_cast<const uint4 *>(src + ks * 32) : make_uint4(0, 0, 0, 0);
+            qf[i][ks] = *reinterpret_cast<bf16x8 *>(&v);
+        }
+    }
+
+    float m_run[RBW], l_run[RBW];
+    f32x4 acc[RBW][VDB];
+#pragma unroll
+    for (int i = 0; i < RBW; ++i) {
+        m_run[i] = -INFINITY; l_run[i] = 0.f;
+#pragma unroll
+        for (int db = 0; db < VDB; ++db) acc[i][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+
+    // ---- tile loader: unit u (16 B) of the tile -> segment u / UNITS_PER_SEG
+    uint4 stage[NLOAD];
+    auto load_tile = [&](int ti) {
+        const int p0 = (tok_begin >> 4) + 2 * ti;
+        const int p1 = (p0 + 1 < npages) ? p0 + 1 : p0;
+        const int pg0 = pt[p0], pg1 = pt[p1];
+#pragma unroll
+        for (int jn = 0; jn < NLOAD; ++jn) {
+            const int u = tid + jn * 256;
+            const int seg = u / UNITS_PER_SEG, off = u % UNITS_PER_SEG;
+            const int pg = (seg & 1) ? pg1 : pg0;
+            const bf16_t *base = (seg < 2 ? kpool : vpool) + ((size_t)pg * Hkv + kvh) * PAGE_E;
+            stage[jn] = reinterpret_cast<const uint4 *>(base)[off];
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int jn = 0; jn < NLOAD; ++jn)
+            *reinterpret_cast<uint4 *>(smem + buf * TILE_B + (tid + jn * 256) * 16) = stage[jn];
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int ti = 0; ti < ntiles; ++ti) {
+        if (ti + 1 < ntiles) load_tile(ti + 1);
+        const unsigned char *cur = smem + (ti & 1) * TILE_B;
+        if (any_active) {
+            const int tile_tok0 = tok_begin + ti * DAS_ATTN_TILE;
+            // S^T = K Q^T : s[i][pg][r] = score of token 16*pg + 4*(lane/16) + r for query row lane%16
+            f32x4 s[RBW][2];
+#pragma unroll
+            for (int i = 0; i < RBW; ++i) { s[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+            for (int ks = 0; ks < KFR; ++ks) {
+                const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(cur + (ks * 64 + lane) * 16);
+                const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
+#pragma unroll
+                for (int i = 0; i < RBW; ++i) {
+                    s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s[i][0], 0, 0, 0);
+                    s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s[i][1], 0, 0, 0);
+                }
+            }
+            const bool need_mask = tile_tok0 + DAS_ATTN_TILE - 1 > ctx;
+            bf16x8 pf[RBW];
+#pragma unroll
+            for (int i = 0; i < RBW; ++i) {
+                float sv[8];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { sv[r] = s[i][0][r] * scale_log2e; sv[4 + r] = s[i][1][r] * scale_log2e; }
+                if (need_mask) {
+                    const int pbase = tile_tok0 + 4 * (lane >> 4);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (pbase + r > lim[i]) sv[r] = -INFINITY;
+                        if (pbase + 16 + r > lim[i]) sv[4 + r] = -INFINITY;
+                    }
+                }
+                float mt = sv[0];
+#pragma unroll
+                for (int r = 1; r < 8; ++r) mt = fmaxf(mt, sv[r]);
+                mt = fmaxf(mt, __shfl_xor(mt, 16));
+                mt = fmaxf(mt, __shfl_xor(mt, 32));
+                const float mn = fmaxf(m_run[i], mt);
+                const float ms = (mn == -INFINITY) ? 0.f : mn;
+                const float alpha = exp2f(m_run[i] - ms);
+                float ps = 0.f;
+                float pv[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) { pv[r] = exp2f(sv[r] - ms); ps += pv[r]; }
+                l_run[i] = l_run[i] * alpha + ps;
+                m_run[i] = mn;
+#pragma unroll
+                for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
+#pragma unroll
+                for (int r = 0; r < 8; ++r) pf[i][r] = (__bf16)pv[r];
+            }
+            // O^T += V^T P^T : A = V fragment (dims x 32 token slots), B = probabilities
+#pragma unroll
+            for (int db = 0; db < VDB; ++db) {
+                const uint2 lo = *reinterpret_cast<const uint2 *>(cur + 2 * PAGE_B + (db * 64 + lane) * 8);
+                const uint2 hi = *reinterpret_cast<const uint2 *>(cur + 3 * PAGE_B + (db * 64 + lane) * 8);
+                uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
+#pragma unroll
+                for (int i = 0; i < RBW; ++i)
+                    acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[i], acc[i][db], 0, 0, 0);
+            }
+        }
+        if (ti + 1 < ntiles) store_tile((ti + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- partial results: (m, l) per row and the un-normalised accumulator
+#pragma unroll
+    for (int i = 0; i < RBW; ++i) {
+        float l = l_run[i];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int rr = (wave * RBW + i) * 16 + (lane & 15);
+        if (rr < R) {
+            const size_t id = ((size_t)pm.b_prow[b] + (size_t)chunk * R + rr) * Hkv + kvh;
+            if ((lane >> 4) == 0) { part_ml[2 * id] = m_run[i]; part_ml[2 * id + 1] = l; }
+            float *dst = part_acc + id * D + 4 * (lane >> 4);
+#pragma unroll
+            for (int db = 0; db < VDB; ++db)
+                *reinterpret_cast<float4 *>(dst + 16 * db) = make_float4(acc[i][db][0], acc[i][db][1], acc[i][db][2], acc[i][db][3]);
+        }
+    }
+}
+
+void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *qkv,
+                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, float *part_acc, float *part_ml,
+                 const DasDims &dm, hipStream_t st) {
+    if (n_items <= 0) return;
+    const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
+    dim3 g(n_items, dm.Hkv), blk(256);
+    const size_t lds = 2 * 4 * (size_t)(DAS_PAGE * dm.D * 2);
+#define ATTN_LAUNCH(DD, RB) \
+    attn_partial_kernel<DD, RB><<<g, blk, lds, st>>>(pm, items, qkv, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.qkvN, sc)
+    if (dm.D == 128) {
+        if (rbw == 1) ATTN_LAUNCH(128, 1); else if (rbw == 2) ATTN_LAUNCH(128, 2); else ATTN_LAUNCH(128, 4);
+    } else {
+        if (rbw == 1) ATTN_LAUNCH(64, 1); else if (rbw == 2) ATTN_LAUNCH(64, 2); else ATTN_LAUNCH(64, 4);
+    }
+#undef ATTN_LAUNCH
+}
+
+// ---------------------------------------------------------------- merge of the chunk partials
+// grid (T, Hq), block 64; ascending chunk order, fp32.  Output: bf16, fragment order, K = Hq*D.
+template <int D>
+__global__ __launch_bounds__(64) void attn_merge_kernel(PassMeta pm, const float *__restrict__ part_acc,
+                                                        const float *__restrict__ part_ml, bf16_t *__restrict__ out,
+                                                        int Hq, int Hkv, int G) {
+    constexpr int E = D / 64;
+    const int t = blockIdx.x, a = blockIdx.y, lane = threadIdx.x;
+    const int b = pm.row_b[t];
+    const int j = t - pm.b_row0[b];
+    const int kvh = a / G, g = a % G;
+    const int R = G * pm.b_n[b], rr = j * G + g;
+    const int last_chunk = (pm.b_start[b] + j) / DAS_ATTN_CHUNK;     // chunks holding positions <= ctx + j
+    float M = -INFINITY, den = 0.f, num[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) num[e] = 0.f;
+    for (int c = 0; c <= last_chunk; ++c) {
+        const size_t id = ((size_t)pm.b_prow[b] + (size_t)c * R + rr) * Hkv + kvh;
+        const float mc = part_ml[2 * id], lc = part_ml[2 * id + 1];
+        if (mc == -INFINITY) continue;
+        const float mn = fmaxf(M, mc);
+        const float a0 = exp2f(M - mn), a1 = exp2f(mc - mn);
+        den = den * a0 + lc * a1;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * a0 + part_acc[id * D + lane * E + e] * a1;
+        M = mn;
+    }
+    const float inv = 1.f / den;
+    const int K = Hq * D;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const float v = num[e] * inv;
+        uint32_t u = __float_as_uint(v);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        out[frag_off(t, a * D + lane * E + e, K)] = (bf16_t)(u >> 16);
+    }
+}
+
+void launch_attn_merge(const PassMeta &pm, const float *part_acc, const float *part_ml, bf16_t *out_frag,
+                       const DasDims &dm, hipStream_t st) {
+    dim3 g(pm.T, dm.Hq), blk(64);
+    if (dm.D == 128) attn_merge_kernel<128><<<g, blk, 0, st>>>(pm, part_acc, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
+    else attn_merge_kernel<64><<<g, blk, 0, st>>>(pm, part_acc, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
+}

@@ -1,0 +1,230 @@
+// Element-wise and data-movement kernels of the verify step: weight repacking,
+// embedding gather, RMSNorm, RoPE + paged KV write, KV import/export.
+#include "das_internal.h"
+
+__device__ __forceinline__ float bf2f(bf16_t x) { return __uint_as_float((uint32_t)x << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);      // round to nearest even
+    return (bf16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------- weight repacking (load time)
+// dst: fragment order [Np/32][Kp/16][64][8]; src row-major [N][K]; zero padding.
+__global__ void pack_weight_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int K, int Np, int Kp) {
+    size_t slot = (size_t)blockIdx.x * blockDim.x + threadIdx.x;        // one 16-byte lane slot
+    size_t total = (size_t)Np * Kp / 8;
+    if (slot >= total) return;
+    int lane = (int)(slot & 63);
+    size_t frag = slot >> 6;
+    int kfr = Kp >> 4;
+    int rb = (int)(frag / kfr), ks = (int)(frag % kfr);
+    int row = rb * 32 + (lane & 31), k0 = ks * 16 + 8 * (lane >> 5);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < N) {
+        if (k0 + 8 <= K && (K & 7) == 0) {
+            v = *reinterpret_cast<const uint4 *>(src + (size_t)row * K + k0);
+        } else {
+            bf16_t t[8];
+            for (int e = 0; e < 8; ++e) t[e] = (k0 + e < K) ? src[(size_t)row * K + k0 + e] : (bf16_t)0;
+            v = *reinterpret_cast<uint4 *>(t);
+        }
+    }
+    reinterpret_cast<uint4 *>(dst)[slot] = v;
+}
+
+// gate and up projections interleaved in groups of 32 output features:
+// packed row n' = b*64 + r  ->  r < 32 ? Wg[b*32 + r] : Wu[b*32 + r - 32]
+__global__ void pack_gateup_kernel(const bf16_t *__restrict__ wg, const bf16_t *__restrict__ wu, bf16_t *__restrict__ dst,
+                                   int F, int K, int Fp) {
+    size_t slot = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)2 * Fp * K / 8;
+    if (slot >= total) return;
+    int lane = (int)(slot & 63);
+    size_t frag = slot >> 6;
+    int kfr = K >> 4;
+    int rb = (int)(frag / kfr), ks = (int)(frag % kfr);
+    int row = rb * 32 + (lane & 31), k0 = ks * 16 + 8 * (lane >> 5);
+    int b = row >> 6, r = row & 63;
+    int feat = b * 32 + (r & 31);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (feat < F) v = *reinterpret_cast<const uint4 *>((r < 32 ? wg : wu) + (size_t)feat * K + k0);
+    reinterpret_cast<uint4 *>(dst)[slot] = v;
+}
+
+void launch_pack_weight(const bf16_t *src, bf16_t *dst, int N, int K, int Np, int Kp, hipStream_t st) {
+    size_t total = (size_t)Np * Kp / 8;
+    pack_weight_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(src, dst, N, K, Np, Kp);
+}
+void launch_pack_gateup(const bf16_t *wg, const bf16_t *wu, bf16_t *dst, int F, int K, int Fp, hipStream_t st) {
+    size_t total = (size_t)2 * Fp * K / 8;
+    pack_gateup_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(wg, wu, dst, F, K, Fp);
+}
+
+// ---------------------------------------------------------------- page-table updates
+__global__ void pt_update_kernel(int *page_table, const int *upd, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) page_table[upd[2 * i]] = upd[2 * i + 1];
+}
+void launch_pt_update(int *page_table, const int *upd, int n_upd, hipStream_t st) {
+    if (n_upd > 0) pt_update_kernel<<<dim3((n_upd + 255) / 256), dim3(256), 0, st>>>(page_table, upd, n_upd);
+}
+
+// ---------------------------------------------------------------- embedding gather: h[r] = E[tok[r]]
+__global__ void embed_kernel(const int *__restrict__ tok, const bf16_t *__restrict__ E, float *__restrict__ h, int d) {
+    int r = blockIdx.x;
+    const bf16_t *src = E + (size_t)tok[r] * d;
+    float *dst = h + (size_t)r * d;
+    for (int c = threadIdx.x; c < d / 8; c += blockDim.x) {
+        uint4 v = reinterpret_cast<const uint4 *>(src)[c];
+        const bf16_t *e = reinterpret_cast<const bf16_t *>(&v);
+        float4 a = make_float4(bf2f(e[0]), bf2f(e[1]), bf2f(e[2]), bf2f(e[3]));
+        float4 b = make_float4(bf2f(e[4]), bf2f(e[5]), bf2f(e[6]), bf2f(e[7]));
+        reinterpret_cast<float4 *>(dst)[2 * c] = a;
+        reinterpret_cast<float4 *>(dst)[2 * c + 1] = b;
+    }
+}
+void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStream_t st) {
+    embed_kernel<<<dim3(pm.T), dim3(256), 0, st>>>(pm.tok, E, h, d);
+}
+
+// ---------------------------------------------------------------- RMSNorm -> bf16, fragment order
+// y = x * rsqrt(mean(x^2) + eps) * g, fp32 accumulation; output row i of the
+// fragment-ordered matrix [n][d] comes from h[sel ? sel[i] : i].
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, const bf16_t *__restrict__ g,
+                                                      bf16_t *__restrict__ y, const int *__restrict__ sel, int d, float eps) {
+    __shared__ float red[4];
+    int i = blockIdx.x;
+    const float *x = h + (size_t)(sel ? sel[i] : i) * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d / 8; c += 256) {
+        float4 a = reinterpret_cast<const float4 *>(x)[2 * c], b = reinterpret_cast<const float4 *>(x)[2 * c + 1];
+        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = red[0] + red[1] + red[2] + red[3];
+    float inv = rsqrtf(tot / (float)d + eps);
+    for (int c = threadIdx.x; c < d / 8; c += 256) {
+        float4 a = reinterpret_cast<const float4 *>(x)[2 * c], b = reinterpret_cast<const float4 *>(x)[2 * c + 1];
+        uint4 gv = reinterpret_cast<const uint4 *>(g)[c];
+        const bf16_t *ge = reinterpret_cast<const bf16_t *>(&gv);
+        bf16_t o[8];
+        o[0] = f2bf(a.x * inv * bf2f(ge[0])); o[1] = f2bf(a.y * inv * bf2f(ge[1]));
+        o[2] = f2bf(a.z * inv * bf2f(ge[2])); o[3] = f2bf(a.w * inv * bf2f(ge[3]));
+        o[4] = f2bf(b.x * inv * bf2f(ge[4])); o[5] = f2bf(b.y * inv * bf2f(ge[5]));
+        o[6] = f2bf(b.z * inv * bf2f(ge[6])); o[7] = f2bf(b.w * inv * bf2f(ge[7]));
+        *reinterpret_cast<uint4 *>(y + frag_off(i, c * 8, d)) = *reinterpret_cast<uint4 *>(o);
+    }
+}
+void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
+    if (n > 0) rmsnorm_kernel<<<dim3(n), dim3(256), 0, st>>>(h, g, y, sel, d, eps);
+}
+
+// ---------------------------------------------------------------- RoPE angles, once per pass
+// cs[r][i] = (cos, sin)(pos_r * inv_freq_i), computed in fp64 so that positions
+// up to 64k lose nothing before the fp32 rotation.
+__global__ void rope_table_kernel(const int *__restrict__ row_pos, const double *__restrict__ inv_freq,
+                                  float2 *__restrict__ cs, int T, int half) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T * half) return;
+    int r = idx / half, i = idx % half;
+    double ang = (double)row_pos[r] * inv_freq[i];
+    double s, c;
+    sincos(ang, &s, &c);
+    cs[idx] = make_float2((float)c, (float)s);
+}
+void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, int D, hipStream_t st) {
+    int n = pm.T * (D / 2);
+    rope_table_kernel<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(pm.row_pos, inv_freq, reinterpret_cast<float2 *>(cs), pm.T, D / 2);
+}
+
+// ---------------------------------------------------------------- RoPE on q (in place) and k; K/V rows -> pages
+// grid (T, Hq + 2 Hkv), block D/2: thread i owns the rotate-half pair (i, i + D/2).
+__global__ void rope_kv_kernel(PassMeta pm, bf16_t *__restrict__ qkv, const float2 *__restrict__ cs,
+                               bf16_t *__restrict__ kpool, bf16_t *__restrict__ vpool, int Hq, int Hkv, int D, int qkvN) {
+    int r = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = D >> 1;
+    bf16_t *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
+    float x1 = bf2f(row[i]), x2 = bf2f(row[i + half]);
+    if (hh < Hq + Hkv) {
+        float2 c = cs[r * half + i];
+        float y1 = x1 * c.x - x2 * c.y, y2 = x2 * c.x + x1 * c.y;
+        x1 = y1; x2 = y2;
+    }
+    if (hh < Hq) { row[i] = f2bf(x1); row[i + half] = f2bf(x2); return; }
+    int b = pm.row_b[r], pos = pm.row_pos[r];
+    int page = pm.page_table[(size_t)pm.b_slot[b] * pm.max_pages + (pos >> 4)];
+    int t = pos & 15;
+    if (hh < Hq + Hkv) {
+        bf16_t *blk = kpool + ((size_t)page * Hkv + (hh - Hq)) * (size_t)(DAS_PAGE * D);
+        blk[kpage_off(t, i)] = f2bf(x1);
+        blk[kpage_off(t, i + half)] = f2bf(x2);
+    } else {
+        bf16_t *blk = vpool + ((size_t)page * Hkv + (hh - Hq - Hkv)) * (size_t)(DAS_PAGE * D);
+        blk[vpage_off(t, i)] = row[i];
+        blk[vpage_off(t, i + half)] = row[i + half];
+    }
+}
+void launch_rope_kv(const PassMeta &pm, bf16_t *qkv, const float *cs, bf16_t *kpool_layer, bf16_t *vpool_layer,
+                    const DasDims &dm, hipStream_t st) {
+    rope_kv_kernel<<<dim3(pm.T, dm.Hq + 2 * dm.Hkv), dim3(dm.D / 2), 0, st>>>(
+        pm, qkv, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
+}
+
+// ---------------------------------------------------------------- KV import / export / synthetic fill
+// linear layout [n_pos][Hkv][D]; grid (n_pos, Hkv), block D
+__global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int first_pos, bf16_t *kpool, bf16_t *vpool,
+                             bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D) {
+    int p = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
+    int pos = first_pos + p;
+    size_t blk = ((size_t)page_row[pos >> 4] * Hkv + hd) * (size_t)(DAS_PAGE * D);
+    size_t lin = ((size_t)p * Hkv + hd) * D + d;
+    int t = pos & 15;
+    if (mode == 0) {
+        kpool[blk + kpage_off(t, d)] = k_lin[lin];
+        vpool[blk + vpage_off(t, d)] = v_lin[lin];
+    } else {
+        k_lin[lin] = kpool[blk + kpage_off(t, d)];
+        v_lin[lin] = vpool[blk + vpage_off(t, d)];
+    }
+}
+void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_t *kpool_layer, bf16_t *vpool_layer,
+                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, hipStream_t st) {
+    if (n_pos > 0)
+        kv_io_kernel<<<dim3(n_pos, Hkv), dim3(D), 0, st>>>(mode, page_row, first_pos, kpool_layer, vpool_layer, k_lin, v_lin, Hkv, D);
+}
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__device__ __forceinline__ bf16_t synth_value(uint64_t base, uint64_t e) {
+    uint64_t h = mix64(base ^ e);
+    int s = (int)(h & 0xFFFF) + (int)((h >> 16) & 0xFFFF) + (int)((h >> 32) & 0xFFFF) + (int)(h >> 48) - 131070;
+    return f2bf((float)s * (1.0f / 32768.0f));
+}
+__global__ void kv_synth_kernel(const int *__restrict__ page_row, bf16_t *kpool, bf16_t *vpool, int Hkv, int D,
+                                uint64_t base_k, uint64_t base_v) {
+    int pos = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
+    size_t blk = ((size_t)page_row[pos >> 4] * Hkv + hd) * (size_t)(DAS_PAGE * D);
+    uint64_t e = ((uint64_t)pos * Hkv + hd) * D + d;
+    int t = pos & 15;
+    kpool[blk + kpage_off(t, d)] = synth_value(base_k, e);
+    vpool[blk + vpage_off(t, d)] = synth_value(base_v, e);
+}
+static uint64_t host_mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D,
+                     uint64_t seed, uint64_t seq_key, int layer, hipStream_t st) {
+    if (ctx <= 0) return;
+    uint64_t b = host_mix64(host_mix64(seed ^ 0x4B5653594E544821ull) ^ seq_key);
+    uint64_t bk = host_mix64(b ^ ((uint64_t)layer * 2u)), bv = host_mix64(b ^ ((uint64_t)layer * 2u + 1u));
+    kv_synth_kernel<<<dim3(ctx, Hkv), dim3(D), 0, st>>>(page_row, kpool_layer, vpool_layer, Hkv, D, bk, bv);
+}

@@ -1,0 +1,176 @@
+// Decision kernels of the verify step: per-row argmax (wavefront reduction,
+// lowest index wins ties), greedy prefix acceptance, and the rejection-sampling
+// acceptance for stochastic rollouts.
+#include "das_internal.h"
+
+// ---------------------------------------------------------------- argmax over the vocabulary
+__global__ __launch_bounds__(1024) void argmax_kernel(const float *__restrict__ logits, int V, int *__restrict__ out) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    const float *x = logits + (size_t)blockIdx.x * V;
+    float best = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    const int nv4 = V >> 2;
+    for (int c = threadIdx.x; c < nv4; c += 1024) {
+        float4 v = reinterpret_cast<const float4 *>(x)[c];
+        int i = c * 4;
+        if (v.x > best) { best = v.x; bi = i; }
+        if (v.y > best) { best = v.y; bi = i + 1; }
+        if (v.z > best) { best = v.z; bi = i + 2; }
+        if (v.w > best) { best = v.w; bi = i + 3; }
+    }
+    for (int i = (nv4 << 2) + threadIdx.x; i < V; i += 1024)
+        if (x[i] > best) { best = x[i]; bi = i; }
+    // thread-local scan is in ascending index, so bi is already the lowest index of its maximum
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(best, o);
+        int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+        out[blockIdx.x] = bi;
+    }
+}
+void launch_argmax(const float *logits, int n_rows, int V, int *out, hipStream_t st) {
+    if (n_rows > 0) argmax_kernel<<<dim3(n_rows), dim3(1024), 0, st>>>(logits, V, out);
+}
+
+// ---------------------------------------------------------------- greedy acceptance
+// Block b holds rows [pending, d_1..d_k]; g[r] is the target's token after row r.
+// accept = longest prefix with d_j == g[row j-1]; next = g[row accept].
+__global__ void accept_greedy_kernel(const int *__restrict__ g, const int *__restrict__ b_row0, const int *__restrict__ b_n,
+                                     const int *__restrict__ tok, int NB, int *__restrict__ accept_len,
+                                     int *__restrict__ next_token) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= NB) return;
+    const int r0 = b_row0[b], k = b_n[b] - 1;
+    int a = 0;
+    while (a < k && tok[r0 + 1 + a] == g[r0 + a]) ++a;
+    accept_len[b] = a;
+    next_token[b] = g[r0 + a];
+}
+void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const int *tok, int NB,
+                          int *accept_len, int *next_token, hipStream_t st) {
+    if (NB > 0) accept_greedy_kernel<<<dim3((NB + 63) / 64), dim3(64), 0, st>>>(g, b_row0, b_n, tok, NB, accept_len, next_token);
+}
+
+// ---------------------------------------------------------------- stochastic acceptance
+// row_stats[r] = (max logit, Z = sum exp((l - max)/T))
+__global__ __launch_bounds__(1024) void row_stats_kernel(const float *__restrict__ logits, int V, float inv_temp,
+                                                         float *__restrict__ stats) {
+    __shared__ float red[16];
+    const float *x = logits + (size_t)blockIdx.x * V;
+    float mx = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += 1024) mx = fmaxf(mx, x[i]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = red[0];
+    for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
+    __syncthreads();
+    float z = 0.f;
+    for (int i = threadIdx.x; i < V; i += 1024) z += __expf((x[i] - mx) * inv_temp);
+    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = z;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int w = 0; w < 16; ++w) t += red[w];
+        stats[2 * blockIdx.x] = mx;
+        stats[2 * blockIdx.x + 1] = t;
+    }
+}
+
+// One workgroup per sequence.  Rows j = 0..k-1: accept draft j+1 iff u_accept*Z < w(draft).
+// Then an inverse-CDF draw (ascending vocabulary order) from the row where the walk stopped,
+// with the rejected draft's weight removed.  Thread t owns the contiguous slice
+// [t*seg, (t+1)*seg) so that the cumulative sum runs in index order.
+__global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__restrict__ logits, int V,
+                                                             const int *__restrict__ tok, const int *__restrict__ b_row0,
+                                                             const int *__restrict__ b_n, float inv_temp,
+                                                             const float *__restrict__ u_accept,
+                                                             const float *__restrict__ u_sample, int prefill_mode,
+                                                             const float *__restrict__ stats, int *__restrict__ accept_len,
+                                                             int *__restrict__ next_token) {
+    __shared__ float part[1024];
+    __shared__ int lastnz[16];
+    __shared__ int result;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int r0 = prefill_mode ? b : b_row0[b];
+    const int k = prefill_mode ? 0 : b_n[b] - 1;
+    int a = 0, rejected = -1;
+    for (; a < k; ++a) {
+        const int r = r0 + a, d = tok[r + 1];
+        const float mx = stats[2 * r], Z = stats[2 * r + 1];
+        const float wd = __expf((logits[(size_t)r * V + d] - mx) * inv_temp);
+        if (!(u_accept[r] * Z < wd)) { rejected = d; break; }
+    }
+    const int r = r0 + a;
+    const float *x = logits + (size_t)r * V;
+    const float mx = stats[2 * r];
+    const float u = prefill_mode ? u_sample[b] : u_sample[r];
+    const int seg = (V + 1023) / 1024;
+    const int lo = tid * seg, hi = min(lo + seg, V);
+    float s = 0.f;
+    int nz = -1;
+    for (int i = lo; i < hi; ++i) {
+        const float w = (i == rejected) ? 0.f : __expf((x[i] - mx) * inv_temp);
+        s += w;
+        if (w > 0.f) nz = i;
+    }
+    part[tid] = s;
+    const int nz_local = nz;
+    for (int o = 32; o > 0; o >>= 1) nz = max(nz, __shfl_xor(nz, o));
+    if ((tid & 63) == 0) lastnz[tid >> 6] = nz;
+    if (tid == 0) result = -1;
+    __syncthreads();
+    // inclusive scan of the 1024 slice sums (Hillis-Steele; fixed order)
+    for (int o = 1; o < 1024; o <<= 1) {
+        float v = (tid >= o) ? part[tid - o] : 0.f;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    const float total = part[1023];
+    const float target = u * total;
+    const float excl = (tid == 0) ? 0.f : part[tid - 1];
+    if (excl <= target && part[tid] > target && lo < hi) {
+        // the crossing is inside this slice (slices with equal prefix are empty of weight)
+        float c = excl;
+        int pick = -1;
+        for (int i = lo; i < hi; ++i) {
+            const float w = (i == rejected) ? 0.f : __expf((x[i] - mx) * inv_temp);
+            c += w;
+            if (c > target) { pick = i; break; }
+        }
+        if (pick < 0) pick = nz_local;        // slice total rounded differently inside the scan
+        if (pick >= 0) atomicMax(&result, pick);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int pick = result;
+        if (pick < 0) {                       // rounding pushed the target past the total: last non-zero weight
+            pick = lastnz[0];
+            for (int w = 1; w < 16; ++w) pick = max(pick, lastnz[w]);
+        }
+        accept_len[b] = a;
+        next_token[b] = pick;
+    }
+}
+
+void launch_sample(const float *logits, int V, const int *tok, const int *b_row0, const int *b_n, int NB,
+                   float inv_temp, const float *u_accept, const float *u_sample, int prefill_mode,
+                   float *row_stats, int *accept_len, int *next_token, hipStream_t st) {
+    // the caller passes the number of logit rows through b_n/b_row0 (verify) or NB (prefill: one row per sequence)
+    (void)row_stats;
+    accept_sample_kernel<<<dim3(NB), dim3(1024), 0, st>>>(logits, V, tok, b_row0, b_n, inv_temp, u_accept, u_sample,
+                                                        prefill_mode, row_stats, accept_len, next_token);
+}
+
+void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, float *stats, hipStream_t st) {
+    if (n_rows > 0) row_stats_kernel<<<dim3(n_rows), dim3(1024), 0, st>>>(logits, V, inv_temp, stats);
+}

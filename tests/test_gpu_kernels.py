@@ -1,0 +1,57 @@
+"""GPU checks of single kernels through the C ABI (MFMA GEMM, KV page layout)."""
+import numpy as np
+import pytest
+
+import das_inputs as di
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def das():
+    import paper_2511_13841_amd as d
+    return d
+
+
+@pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256)])
+def test_mfma_gemm_against_fp64(das, M, N, K):
+    rng = np.random.default_rng(M * 7 + N)
+    a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    w = di.f32_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
+    print(f"gemm M={M} N={N} K={K}", flush=True)
+    c = das.debug_gemm(a, w)
+    ref = di.bf16_to_f32(a).astype(np.float64) @ di.bf16_to_f32(w).astype(np.float64).T
+    # fp32 accumulation of exact bf16 products: error ~ sqrt(K) * eps_fp32 * |terms|
+    np.testing.assert_allclose(c, ref, rtol=0, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
+
+
+def _small_model(das, shape, **kw):
+    args = dict(max_seqs=8, max_ctx=4096, max_rows=256, max_draft=8, num_pages=1024)
+    args.update(kw)
+    cfg = das.config_for(shape, **args)
+    return das.DasModel(cfg, di.weights_bf16(shape, seed=0))
+
+
+@pytest.mark.parametrize("model", ["tiny", "hd128"])
+def test_kv_synth_import_export_are_bit_exact(das, model):
+    shape = di.MODELS["tiny"] if model == "tiny" else di.MODELS["tiny"].replace(n_q_heads=6, n_kv_heads=2, head_dim=128, d_model=256)
+    dm = _small_model(das, shape)
+    ctx = 1000
+    dm.seq_create(5, ctx, 3)
+    print("kv_synth", model, flush=True)
+    dm.kv_synth(5, seed=42, seq_key=9)
+    for layer in range(shape.n_layers):
+        k, v = dm.kv_export(5, layer, 0, ctx)
+        np.testing.assert_array_equal(k, di.kv_synth(42, 9, layer, 0, 0, ctx, shape.n_kv_heads, shape.head_dim))
+        np.testing.assert_array_equal(v, di.kv_synth(42, 9, layer, 1, 0, ctx, shape.n_kv_heads, shape.head_dim))
+    # import a window, read it back, neighbours untouched
+    rng = np.random.default_rng(0)
+    kk = rng.integers(0, 1 << 15, size=(37, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+    vv = rng.integers(0, 1 << 15, size=(37, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+    dm.kv_import(5, 1, 100, kk, vv)
+    k, v = dm.kv_export(5, 1, 90, 60)
+    np.testing.assert_array_equal(k[10:47], kk)
+    np.testing.assert_array_equal(v[10:47], vv)
+    np.testing.assert_array_equal(k[:10], di.kv_synth(42, 9, 1, 0, 90, 10, shape.n_kv_heads, shape.head_dim))
+    np.testing.assert_array_equal(v[47:], di.kv_synth(42, 9, 1, 1, 137, 13, shape.n_kv_heads, shape.head_dim))
+    dm.free()
