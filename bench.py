@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Throughput of the batched speculative-verification step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3]
+
+A "step" is one whole round of the hot path over one batch of synthetic input:
+das_verify_step (ragged (1+k_i)-row forward over the paged KV, acceptance) followed
+by das_kv_commit of its own decisions.  Contexts, weights and drafts are seeded
+and synthetic (das_inputs); nothing is read from disk.  One JSON line is printed.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import das_inputs as di                      # noqa: E402
+
+HBM_PEAK_GBS = 8000.0                        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0               # MI355X dense bf16 MFMA, published
+RIDGE_ROWS = 312                             # rows above which a weight GEMM is MFMA- rather than HBM-bound
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Rollout:
+    """A batch of sequences on the GPU plus the synthetic drafter that feeds it."""
+
+    def __init__(self, wl, batch=None, n_layers=None, context="synth", seed=None, max_steps=32):
+        import paper_2511_13841_amd as das
+        self.das = das
+        self.wl = wl
+        shape = di.MODELS[wl.model]
+        if n_layers is not None:
+            shape = shape.replace(n_layers=n_layers)
+        self.shape = shape
+        self.B = wl.batch if batch is None else batch
+        self.seed = wl.seed if seed is None else seed
+        self.ctx0 = di.context_lengths(wl, batch=self.B, seed=self.seed)
+        self.kmax = {"k4": 4, "k16": 16, "quartile": 16, "loglen": 32}[wl.budgets]
+        grow = max_steps * (self.kmax + 1) + self.kmax + 2
+        self.horizon = grow
+        pages = int(sum(-(-(int(c) + grow) // 16) for c in self.ctx0)) + 64
+        max_ctx = -(-(int(self.ctx0.max()) + grow + 16) // 16) * 16
+        max_rows = max(self.B * (self.kmax + 1), 256)
+        t0 = time.time()
+        self.blob = di.weights_bf16(shape, seed=0)
+        log(f"[bench] weights {self.blob.size * 2 / 1e9:.2f} GB generated in {time.time() - t0:.1f}s")
+        t0 = time.time()
+        self.dm = das.DasModel(das.config_for(shape, max_seqs=self.B, max_ctx=max_ctx, max_rows=max_rows,
+                                              max_draft=self.kmax, num_pages=pages), self.blob)
+        log(f"[bench] model loaded in {time.time() - t0:.1f}s; KV pool {pages} pages "
+            f"({pages * 16 * shape.kv_bytes_per_token / 1e9:.1f} GB)")
+        self.ids = list(range(self.B))
+        rng = np.random.default_rng(self.seed + 17)
+        t0 = time.time()
+        if context == "prefill":
+            prompts = di.prompts(self.ctx0, shape.vocab, self.seed)
+            self.pending0 = self.dm.prefill(self.ids, prompts)
+        else:
+            self.pending0 = rng.integers(0, shape.vocab, size=self.B, dtype=np.int32)
+            for i in self.ids:
+                self.dm.seq_create(i, int(self.ctx0[i]), int(self.pending0[i]))
+                self.dm.kv_synth(i, self.seed, i)
+        log(f"[bench] contexts ({context}): {int(self.ctx0.sum())} tokens in {time.time() - t0:.1f}s")
+        self.ctx = self.ctx0.copy()
+        self.pending = self.pending0.copy()
+        self.future = None
+
+    def generate_trajectories(self):
+        """Plain decoding (k=0 verify steps) for `horizon` tokens, then rewind.  future[i][0] is the pending token."""
+        t0 = time.time()
+        fut = np.empty((self.B, self.horizon + 1), np.int32)
+        fut[:, 0] = self.pending0
+        empty = [[] for _ in self.ids]
+        for t in range(self.horizon):
+            acc, nxt = self.dm.verify_step(self.ids, self.ctx0 + t, empty)
+            self.dm.kv_commit(self.ids, acc, nxt)
+            fut[:, t + 1] = nxt
+        self.dm.seq_rewind(self.ids, self.ctx0, self.pending0)
+        self.future = fut
+        # the drafter's proposals: the true continuation with every position independently kept with
+        # probability p (a contiguous copy out of this buffer is what a suffix match would return)
+        rng = np.random.default_rng(self.seed + 29)
+        bad = rng.random(fut.shape) >= self.wl.accept_p
+        self.proposal = np.where(bad, rng.integers(0, self.shape.vocab, size=fut.shape, dtype=np.int32), fut)
+        self.emitted = np.ones(self.B, np.int64)       # trajectory tokens decided so far (the pending one)
+        log(f"[bench] {self.horizon} plain decode steps for the drafter in {time.time() - t0:.1f}s "
+            f"({(time.time() - t0) / self.horizon * 1e3:.2f} ms/step)")
+
+    def step(self, sampling=None):
+        ks = di.draft_budgets(self.wl, self.ctx)
+        drafts = [self.proposal[i, self.emitted[i]:self.emitted[i] + ks[i]] for i in range(self.B)]
+        acc, nxt = self.dm.verify_step(self.ids, self.ctx, drafts, sampling)
+        self.dm.kv_commit(self.ids, acc, nxt)
+        self.ctx = self.ctx + 1 + acc
+        self.emitted += 1 + acc
+        self.pending = nxt
+        return ks, acc, nxt
+
+    def step_shape(self):
+        ks = di.draft_budgets(self.wl, self.ctx)
+        return int((ks + 1).sum()), int((self.ctx.astype(np.int64) + 1 + ks).sum())
+
+
+def kernel_rooflines(shape, prof, T, kv_tokens, n_steps):
+    """Per kernel class: ms per launch, algorithmic bytes / flops per launch, achieved rate, fraction of peak."""
+    d, qd, kd, Fp, V = shape.d_model, shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim, \
+        -(-shape.d_ffn // 64) * 64, shape.vocab
+    gemms = {"gemm_qkv": ((qd + 2 * kd), d), "gemm_o": (d, qd), "gemm_gateup_silu": (2 * shape.d_ffn, d),
+             "gemm_down": (d, shape.d_ffn), "gemm_lm_head": (V, d)}
+    out = {}
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        per = ms / n
+        e = {"ms_per_launch": per, "launches_per_step": n / n_steps, "ms_per_step": ms / n_steps}
+        if name in gemms:
+            N, K = gemms[name]
+            flops, wbytes = 2.0 * T * N * K, 2.0 * N * K
+            if T >= RIDGE_ROWS:
+                e.update(bound="mfma", achieved=flops / per / 1e9, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s")
+            else:
+                e.update(bound="hbm", achieved=wbytes / per / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
+        elif name == "attention":
+            # KV of every visible position read once per layer + the new rows' K/V, q in, partials out not counted
+            b = kv_tokens * 2.0 * kd * 2
+            e.update(bound="hbm", achieved=b / per / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
+        else:
+            out[name] = e
+            continue
+        e["frac"] = e["achieved"] / e["peak"]
+        out[name] = e
+    return out
+
+
+def cpu_baseline(ro, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the same step: the first sequences of the batch
+    (batch order is already random) with synthetic KV of the same generator, one verify round each."""
+    import oracle
+    shape = ro.shape
+    t0 = time.time()
+    om = oracle.OracleModel(shape, di.bf16_to_f32(ro.blob))
+    log(f"[bench] oracle weights widened in {time.time() - t0:.1f}s")
+    ks = di.draft_budgets(ro.wl, ro.ctx0)
+    flops_per_row = 2.0 * shape.streamed_params
+    rows, tokens, secs, used = 0, 0, 0.0, []
+    order = np.argsort(ro.ctx0, kind="stable")           # shortest first: bounded memory and time
+    est_rate = 15e9 * oracle.num_threads()               # only to size the sample before the first timing
+    for i in order:
+        k = int(ks[i])
+        if secs + (1 + k) * flops_per_row / est_rate > budget_s and used:
+            break
+        c = int(ro.ctx0[i])
+        s = om.new_seq(c + k + 1)
+        for layer in range(shape.n_layers):
+            s.kv(layer, 0)[:c] = di.bf16_to_f32(di.kv_synth(ro.seed, int(i), layer, 0, 0, c, shape.n_kv_heads, shape.head_dim))
+            s.kv(layer, 1)[:c] = di.bf16_to_f32(di.kv_synth(ro.seed, int(i), layer, 1, 0, c, shape.n_kv_heads, shape.head_dim))
+        s.len, s.pending = c, int(ro.pending0[i])
+        drafts = ro.proposal[i, 1:1 + k]
+        t1 = time.time()
+        a, nxt, _ = om.verify_greedy(s, drafts)
+        dt = time.time() - t1
+        secs += dt
+        rows += 1 + k
+        tokens += a + 1
+        used.append(int(i))
+        est_rate = rows * flops_per_row / secs
+        s.close()
+        if secs > budget_s:
+            break
+    om.close()
+    return {"value": tokens / secs, "unit": "emitted tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{len(used)} shortest sequences of the batch ({rows} rows, synthetic KV), one verify round each, "
+                      f"{secs:.1f}s of CPU time"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--context", default="synth", choices=["synth", "prefill"])
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (sequences shard by data parallelism without any "
+                 "exchange; there is no multi-GPU path to time).  Use --gpus 1.")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs an MI355X; no HIP device is visible")
+    wl = di.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+    ro = Rollout(wl, batch=args.batch, n_layers=args.layers, context=args.context, max_steps=W + 2 * K + 1)
+    ro.generate_trajectories()
+
+    for _ in range(W):
+        ro.step()
+    torch.cuda.synchronize()
+    emitted = accepted = rows = 0
+    t0 = time.perf_counter()
+    for _ in range(K):
+        ks, acc, _ = ro.step()
+        emitted += int((acc + 1).sum()); accepted += int(acc.sum()); rows += int((ks + 1).sum())
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    roof, kernels, ms_prof = None, None, None
+    if not args.no_profile:
+        # the same K steps again, every launch bracketed by HIP events on the library's stream
+        ro.dm.profile_enable(True)
+        ro.dm.profile_reset()
+        Tsum = kvsum = 0
+        t1 = time.perf_counter()
+        for _ in range(K):
+            T, kv = ro.step_shape()
+            Tsum += T; kvsum += kv
+            ro.step()
+        ms_prof = (time.perf_counter() - t1) / K * 1e3
+        prof = ro.dm.profile_read()
+        ro.dm.profile_enable(False)
+        kernels = kernel_rooflines(ro.shape, prof, Tsum / K, kvsum / K, K)
+        cand = {k: v for k, v in kernels.items() if "frac" in v}
+        dom = max(cand, key=lambda k: cand[k]["ms_per_step"])
+        e = cand[dom]
+        roof = {"kernel": dom, "bound": e["bound"], "achieved": e["achieved"], "peak": e["peak"], "unit": e["unit"],
+                "frac": e["frac"], "traffic": None, "ms_per_launch": e["ms_per_launch"],
+                "share_of_step": e["ms_per_step"] / sum(v["ms_per_step"] for v in kernels.values())}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(ro)
+
+    out = {
+        "metric": "accepted tokens/s per MI355X in batched spec-verify; % of HBM roofline",
+        "value": emitted / dt, "unit": "emitted tokens/s (accepted drafts + the target's own token per round)",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt / K * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.model} decoder, batch {ro.B}, lengths {wl.lengths}, budgets {wl.budgets}, "
+                               f"drafter acceptance p={wl.accept_p}, context={args.context}"
+                               + (f", layers={args.layers}" if args.layers else ""),
+                   "rows_per_step": rows / K, "kv_tokens": int(ro.ctx0.sum())},
+        "accepted_draft_tokens_per_s": accepted / dt,
+        "mean_accept_len": accepted / (K * ro.B),
+        "roofline": roof, "cpu_baseline": cpu,
+        "ms_per_step_with_events": ms_prof, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

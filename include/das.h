@@ -109,6 +109,10 @@ int das_kv_commit(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t
                   const int32_t *next_tokens);
 /* Discard every row of the pending step; ctx_len and the pending token are unchanged. */
 int das_kv_rollback(das_model *m, int32_t n, const int32_t *seq_ids);
+/* Truncate COMMITTED sequences to an earlier committed length new_lens[i] <= ctx_len (KV beyond it is
+ * discarded, pages returned) and set their pending tokens: replaying a rollout from a checkpoint. */
+int das_seq_rewind(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *new_lens,
+                   const int32_t *pending_tokens);
 /* Release sequences (any state) and their pages. */
 int das_seq_free(das_model *m, int32_t n, const int32_t *seq_ids);
 

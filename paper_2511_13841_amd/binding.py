@@ -49,6 +49,7 @@ def lib():
             "das_kv_commit": [P, I, VP, VP, VP],
             "das_kv_rollback": [P, I, VP],
             "das_seq_free": [P, I, VP],
+            "das_seq_rewind": [P, I, VP, VP, VP],
             "das_seq_create": [P, I, I, I],
             "das_kv_import": [P, I, I, I, I, VP, VP],
             "das_kv_export": [P, I, I, I, I, VP, VP],
@@ -185,6 +186,10 @@ class DasModel:
     def seq_free(self, seq_ids):
         ids = _i32(seq_ids)
         _chk(lib().das_seq_free(self.h, len(ids), ids.ctypes.data), "das_seq_free")
+
+    def seq_rewind(self, seq_ids, new_lens, pending_tokens):
+        ids, l, t = _i32(seq_ids), _i32(new_lens), _i32(pending_tokens)
+        _chk(lib().das_seq_rewind(self.h, len(ids), ids.ctypes.data, l.ctypes.data, t.ctypes.data), "das_seq_rewind")
 
     def seq_create(self, seq_id, ctx_len, pending):
         _chk(lib().das_seq_create(self.h, int(seq_id), int(ctx_len), int(pending)), "das_seq_create")

@@ -650,6 +650,27 @@ extern "C" int das_kv_rollback(das_model *m, int32_t n, const int32_t *seq_ids) 
     return DAS_OK;
 }
 
+extern "C" int das_seq_rewind(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *new_lens,
+                              const int32_t *pending_tokens) {
+    if (!m || n < 0) return DAS_ERR_INVALID;
+    if (n == 0) return DAS_OK;
+    if (!seq_ids || !new_lens || !pending_tokens || !unique_ids(n, seq_ids)) return DAS_ERR_INVALID;
+    std::vector<int> slot(n);
+    for (int i = 0; i < n; ++i) {
+        slot[i] = find_slot(m, seq_ids[i]);
+        if (slot[i] < 0) return DAS_ERR_INVALID;
+        const Seq &s = m->slots[slot[i]];
+        if (s.state != SEQ_COMMITTED) return DAS_ERR_STATE;
+        if (new_lens[i] < 0 || new_lens[i] > s.ctx || pending_tokens[i] < 0 || pending_tokens[i] >= m->dm.V) return DAS_ERR_INVALID;
+    }
+    for (int i = 0; i < n; ++i) {
+        Seq &s = m->slots[slot[i]];
+        s.ctx = new_lens[i]; s.pending = pending_tokens[i];
+        shrink_pages(m, slot[i], s.ctx);
+    }
+    return DAS_OK;
+}
+
 extern "C" int das_seq_free(das_model *m, int32_t n, const int32_t *seq_ids) {
     if (!m || n < 0) return DAS_ERR_INVALID;
     if (n == 0) return DAS_OK;
