@@ -1,0 +1,134 @@
+"""Stochastic verification (rejection sampling with seeded uniforms) on the GPU against the oracle."""
+import numpy as np
+import pytest
+
+import das_inputs as di
+import oracle
+from oracle import softmax_weights
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_sampled_token(w, u, v, eps):
+    """v must satisfy u*Z in [prefix(v-1) - eps*Z, prefix(v) + eps*Z] under the oracle's weights."""
+    cs = np.cumsum(w)
+    Z = cs[-1]
+    lo = cs[v - 1] if v > 0 else 0.0
+    assert w[v] > 0.0, "sampled a zero-weight token"
+    assert lo - eps * Z <= u * Z <= cs[v] + eps * Z, (v, u * Z, lo, cs[v], eps * Z)
+
+
+@pytest.mark.parametrize("mode,tau", [("faithful", 1.0), ("controlled", 1.0), ("controlled", 0.6)])
+def test_rejection_sampling_decisions_match_oracle(mode, tau):
+    import paper_2511_13841_amd as das
+    shape = di.MODELS["tiny"]
+    blob = di.weights_bf16(shape, seed=0, sigma=0.06)          # sharper logits than config 1: p_max ~ 0.05
+    om = oracle.OracleModel(shape, di.bf16_to_f32(blob))
+    dm = das.DasModel(das.config_for(shape, max_seqs=8, max_ctx=1024, max_rows=256, max_draft=8, num_pages=256), blob)
+    lens = [20, 33, 47, 64, 16]
+    ids = list(range(5))
+    prompts = di.prompts(lens, shape.vocab, 55)
+    us0 = di.uniforms(9, ids, [l - 1 for l in lens], 1)
+    nxt = dm.prefill(ids, prompts, sampling=(tau, None, us0))
+    seqs = []
+    for i, p in enumerate(prompts):
+        s = om.new_seq(400)
+        lo = om.prefill(s, p)
+        w, _ = softmax_weights(lo, tau)
+        _check_sampled_token(w, float(us0[i]), int(nxt[i]), 0.02)
+        s.pending = int(nxt[i])
+        seqs.append(s)
+    rng = np.random.default_rng(7)
+    flagged = exact = 0
+    for rnd in range(10):
+        ks = [int(k) for k in rng.integers(0, 7, size=5)]
+        drafts, ua, us = [], [], []
+        for i, s in enumerate(seqs):
+            # likely drafts: the target's own argmax chain with noise
+            d = rng.integers(0, shape.vocab, size=ks[i], dtype=np.int32)
+            for j in range(ks[i]):
+                if rng.random() < 0.7:
+                    d[j] = int(np.argmax(om.verify_logits(s, d[:j])[j]))
+            drafts.append(d)
+            pos = np.arange(s.len, s.len + ks[i] + 1)
+            a_u = di.uniforms(9, [ids[i]] * len(pos), pos, 0)
+            if mode == "controlled":
+                a_u = np.where(rng.random(len(pos)) < 0.7, 0.0, a_u).astype(np.float32)   # u = 0 forces acceptance
+            ua.append(a_u)
+            us.append(di.uniforms(9, [ids[i]] * len(pos), pos, 1))
+        print("round", rnd, ks, flush=True)
+        acc, nx = dm.verify_step(ids, [s.len for s in seqs], drafts, sampling=(tau, np.concatenate(ua), np.concatenate(us)))
+        glog = dm.debug_logits()
+        r0, o_acc, o_nx = 0, [], []
+        for i, s in enumerate(seqs):
+            n = ks[i] + 1
+            a, t, lo = om.verify_stochastic(s, drafts[i], tau, ua[i], us[i])
+            err = np.abs(glog[r0:r0 + n] - lo).max()
+            assert err <= 3e-2 * np.abs(lo).max()
+            delta = float(err) / tau
+            # a decision is flagged when a uniform lies within e^{+-0.1} of the accept probability on the way
+            flag = False
+            for j in range(min(a + 1, ks[i])):
+                w, Z = softmax_weights(lo[j], tau)
+                pd = w[drafts[i][j]] / Z
+                if pd * np.exp(-0.1) <= ua[i][j] <= pd * np.exp(0.1):
+                    flag = True
+            if flag:
+                flagged += 1
+            else:
+                exact += 1
+                assert int(acc[i]) == a, (rnd, i, int(acc[i]), a)
+                w, _ = softmax_weights(lo[a], tau)
+                if a < ks[i]:
+                    w = w.copy(); w[drafts[i][a]] = 0.0
+                    assert int(nx[i]) != int(drafts[i][a])
+                _check_sampled_token(w, float(us[i][a]), int(nx[i]), np.exp(2 * delta) - 1 + 1e-6)
+            om.commit(s, a, t, drafts[i])
+            o_acc.append(a); o_nx.append(t)
+            r0 += n
+        dm.kv_commit(ids, o_acc, o_nx)
+    print("exact", exact, "flagged", flagged)
+    assert exact > 30
+    if mode == "controlled":
+        assert sum(s.len for s in seqs) - sum(lens) > 60      # forced acceptances really advance the sequences
+    dm.free()
+
+
+def test_first_emitted_token_distribution_chi_square_on_gpu():
+    """Vocabulary 32, 64 copies of one state, fresh uniforms every call: the first emitted token of the
+    speculative round follows softmax(logits/T) of the target (the rule is distribution-preserving)."""
+    from scipy.stats import chi2
+    import paper_2511_13841_amd as das
+    shape = di.ModelShape("v32", 1, 64, 2, 1, 64, 64, 32, rope_theta=1.0e4)
+    blob = di.weights_bf16(shape, seed=3, sigma=0.3)
+    om = oracle.OracleModel(shape, di.bf16_to_f32(blob))
+    B, tau = 64, 0.8
+    dm = das.DasModel(das.config_for(shape, max_seqs=B, max_ctx=64, max_rows=B * 3, max_draft=2, num_pages=B * 2), blob)
+    prompt = di.prompts([9], shape.vocab, 2)[0]
+    ids = list(range(B))
+    dm.prefill(ids, [prompt] * B)
+    dm.seq_rewind(ids, [9] * B, [5] * B)            # same pending token everywhere
+    s = om.new_seq(32)
+    om.prefill(s, prompt)
+    s.pending = 5
+    lo = om.verify_logits(s, [])[0]
+    w, Z = softmax_weights(lo, tau)
+    p = w / Z
+    d1 = int(np.argmax(p))
+    rng = np.random.default_rng(1234)
+    hist = np.zeros(shape.vocab)
+    n_acc = 0
+    rounds = 150
+    for r in range(rounds):
+        ua, us = rng.random(3 * B).astype(np.float32), rng.random(3 * B).astype(np.float32)
+        acc, nx = dm.verify_step(ids, [9] * B, [[d1, 7]] * B, sampling=(tau, ua, us))
+        dm.kv_rollback(ids)
+        for i in range(B):
+            hist[d1 if acc[i] >= 1 else nx[i]] += 1
+            n_acc += int(acc[i] >= 1)
+    n = rounds * B
+    stat = float(((hist - n * p) ** 2 / (n * p)).sum())
+    print("chi2", stat, "accept rate", n_acc / n, "p(d1)", p[d1])
+    assert chi2.sf(stat, shape.vocab - 1) > 1e-3, stat
+    assert abs(n_acc / n - p[d1]) < 4 * np.sqrt(p[d1] * (1 - p[d1]) / n) + 0.01
+    dm.free()
