@@ -17,7 +17,15 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
     return (bf16_t)(u >> 16);
 }
 
+// 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at lds + 16*l.
+__device__ __forceinline__ void dma16(const void *g, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
 // WGM x WGN waves, each owning TM x TN blocks of 32x32.  BK = 64 (4 MFMA k-steps).
+// Two k-tile stages live in two separate LDS arrays so that the compiler can tell the stage being
+// filled by the DMA from the stage being read, and lets the copy run under the MFMAs.
 template <int WGM, int WGN, int TM, int TN, int EPI>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
@@ -27,8 +35,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     constexpr int A_UNITS = AB * 256, B_UNITS = BB * 256; // 16-byte units per k-tile
     constexpr int NLOAD = (A_UNITS + B_UNITS) / NT;
     static_assert((A_UNITS + B_UNITS) % NT == 0, "tile must divide evenly over the threads");
+    static_assert(A_UNITS % NT == 0, "A/W split must fall on a whole pass over the threads");
     constexpr int STAGE_BYTES = (AB + BB) * 4096;
-    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ __align__(16) unsigned char stage0[STAGE_BYTES];
+    __shared__ __align__(16) unsigned char stage1[STAGE_BYTES];
 
     // XCD-aware tile order: the workgroups of one XCD (id % 8) walk a contiguous
     // run of tiles, M fastest, so tiles sharing a weight tile share an L2.
@@ -38,29 +48,20 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     if (t >= nt) return;
     const int tile_m = t % tiles_m, tile_n = t / tiles_m;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int KF = K >> 4;                                 // fragments per row block
     const int KT = K >> 6;                                 // k-tiles
     const uint4 *Ag = reinterpret_cast<const uint4 *>(A);
     const uint4 *Wg = reinterpret_cast<const uint4 *>(W);
 
-    // per-thread source units: unit u < A_UNITS comes from A, else from W
-    static_assert(A_UNITS % NT == 0, "A/W split must fall on a whole pass over the threads");
-    size_t src_base[NLOAD];
-    int lds_off[NLOAD];
+    // per-thread source of each 16-byte unit u = tid + j*NT: units below A_UNITS come from A, the rest from W
+    const uint4 *src[NLOAD];
 #pragma unroll
     for (int j = 0; j < NLOAD; ++j) {
-        int u = tid + j * NT;
-        if (u < A_UNITS) {
-            int blk = u >> 8, off = u & 255;
-            src_base[j] = ((size_t)(tile_m * AB + blk) * KF) * 64 + off;      // in uint4 units (64 per fragment)
-        } else {
-            int v = u - A_UNITS;
-            int blk = v >> 8, off = v & 255;
-            src_base[j] = ((size_t)(tile_n * BB + blk) * KF) * 64 + off;
-        }
-        lds_off[j] = u * 16;
+        const int u = tid + j * NT;
+        if (j * NT < A_UNITS) src[j] = Ag + ((size_t)(tile_m * AB + (u >> 8)) * KF) * 64 + (u & 255);
+        else { const int v = u - A_UNITS; src[j] = Wg + ((size_t)(tile_n * BB + (v >> 8)) * KF) * 64 + (v & 255); }
     }
 
     f32x16 acc[TM][TN];
@@ -71,22 +72,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 stage[NLOAD];
+    auto issue = [&](int kt, unsigned char *stage) {       // 4 fragments = 256 uint4 per k-tile and row block
 #pragma unroll
-    for (int j = 0; j < NLOAD; ++j) stage[j] = (j * NT < A_UNITS) ? Ag[src_base[j]] : Wg[src_base[j]];
-#pragma unroll
-    for (int j = 0; j < NLOAD; ++j) *reinterpret_cast<uint4 *>(smem + lds_off[j]) = stage[j];
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const unsigned char *cur = smem + (kt & 1) * STAGE_BYTES;
-        if (kt + 1 < KT) {
-#pragma unroll
-            for (int j = 0; j < NLOAD; ++j) {
-                size_t s = src_base[j] + (size_t)(kt + 1) * 256;              // 4 fragments = 256 uint4 per k-tile
-                stage[j] = (j * NT < A_UNITS) ? Ag[s] : Wg[s];
-            }
-        }
+        for (int j = 0; j < NLOAD; ++j) dma16(src[j] + (size_t)kt * 256, stage + j * NT * 16 + wave * 1024);
+    };
+    auto compute = [&](const unsigned char *cur) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             bf16x8 a[TM], b[TN];
@@ -106,12 +96,20 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
                 }
         }
-        if (kt + 1 < KT) {
-            unsigned char *nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-#pragma unroll
-            for (int j = 0; j < NLOAD; ++j) *reinterpret_cast<uint4 *>(nxt + lds_off[j]) = stage[j];
-        }
-        __syncthreads();
+    };
+    auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); };
+
+    issue(0, stage0);
+    landed();
+    for (int kt = 0;; kt += 2) {                           // even k-tiles in stage0, odd ones in stage1
+        if (kt + 1 < KT) issue(kt + 1, stage1);
+        compute(stage0);
+        if (kt + 1 >= KT) break;
+        landed();
+        if (kt + 2 < KT) issue(kt + 2, stage0);
+        compute(stage1);
+        if (kt + 2 >= KT) break;
+        landed();
     }
 
     const int m0 = tile_m * AB * 32 + wm * TM * 32, n0 = tile_n * BB * 32 + wn * TN * 32;
@@ -166,7 +164,7 @@ static void launch_cfg(int epi, const bf16_t *A, const bf16_t *W, void *C, int M
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int nt = tiles_m * tiles_n;
     const int grid = ((nt + 7) / 8) * 8;
-    const size_t lds = 2 * (size_t)(WGM * TM + WGN * TN) * 4096;
+    const size_t lds = 0;     // the two k-tile stages are static LDS arrays
     dim3 g(grid), b(WGM * WGN * 64);
     switch (epi) {
     case EPI_BF16_ROWMAJOR:
