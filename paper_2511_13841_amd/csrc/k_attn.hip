@@ -21,6 +21,12 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at lds + 16*l.
+__device__ __forceinline__ void dma16(const void *g, void *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
 template <int D, int RBW>
 __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const bf16_t *__restrict__ qkv,
@@ -35,11 +41,14 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
     constexpr int TILE_B = 4 * PAGE_B;     // K page0, K page1, V page0, V page1
     constexpr int UNITS_PER_SEG = PAGE_B / 16;
     constexpr int NLOAD = (TILE_B / 16) / 256;
-    extern __shared__ __align__(16) unsigned char smem[];
+    // three tile stages in three separate LDS arrays: one being read, two being filled by the DMA
+    __shared__ __align__(16) unsigned char st0[TILE_B];
+    __shared__ __align__(16) unsigned char st1[TILE_B];
+    __shared__ __align__(16) unsigned char st2[TILE_B];
 
     const int b = items[2 * blockIdx.x], chunk = items[2 * blockIdx.x + 1];
     const int kvh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ctx = pm.b_start[b], n = pm.b_n[b], row0 = pm.b_row0[b];
     const int R = G * n;
     const int tok_begin = chunk * DAS_ATTN_CHUNK;
@@ -48,6 +57,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
     const int ntiles = (tok_end - tok_begin + DAS_ATTN_TILE - 1) / DAS_ATTN_TILE;
     const int npages = (tok_total + DAS_PAGE - 1) / DAS_PAGE;
     const int *pt = pm.page_table + (size_t)pm.b_slot[b] * pm.max_pages;
+    // the chunk's (at most 64) page ids, one per lane, fetched once: the tile loop then takes them with
+    // v_readlane and never waits on a vector load of its own (which would also wait for every copy in flight)
+    const int first_page = tok_begin >> 4;
+    const int my_page = pt[min(first_page + lane, npages - 1)];
 
     // ---- query fragments (B operand: lane l = query row l%16, dims 8*(l/16)..+7 of each 32-dim step)
     bf16x8 qf[RBW][KFR];
@@ -77,99 +90,113 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
         for (int db = 0; db < VDB; ++db) acc[i][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- tile loader: unit u (16 B) of the tile -> segment u / UNITS_PER_SEG
-    uint4 stage[NLOAD];
-    auto load_tile = [&](int ti) {
-        const int p0 = (tok_begin >> 4) + 2 * ti;
-        const int p1 = (p0 + 1 < npages) ? p0 + 1 : p0;
-        const int pg0 = pt[p0], pg1 = pt[p1];
+    // ---- tile loader: 16-byte unit u of the tile belongs to segment u / UNITS_PER_SEG
+    auto issue = [&](int ti, unsigned char *stage) {
+        const int pg0 = __builtin_amdgcn_readlane(my_page, 2 * ti);
+        const int pg1 = __builtin_amdgcn_readlane(my_page, 2 * ti + 1);     // clamped to the last page at load
 #pragma unroll
         for (int jn = 0; jn < NLOAD; ++jn) {
             const int u = tid + jn * 256;
             const int seg = u / UNITS_PER_SEG, off = u % UNITS_PER_SEG;
             const int pg = (seg & 1) ? pg1 : pg0;
             const bf16_t *base = (seg < 2 ? kpool : vpool) + ((size_t)pg * Hkv + kvh) * PAGE_E;
-            stage[jn] = reinterpret_cast<const uint4 *>(base)[off];
+            dma16(reinterpret_cast<const uint4 *>(base) + off, stage + jn * 4096 + wave * 1024);
         }
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int jn = 0; jn < NLOAD; ++jn)
-            *reinterpret_cast<uint4 *>(smem + buf * TILE_B + (tid + jn * 256) * 16) = stage[jn];
-    };
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int ti = 0; ti < ntiles; ++ti) {
-        if (ti + 1 < ntiles) load_tile(ti + 1);
-        const unsigned char *cur = smem + (ti & 1) * TILE_B;
-        if (any_active) {
-            const int tile_tok0 = tok_begin + ti * DAS_ATTN_TILE;
-            // S^T = K Q^T : s[i][pg][r] = score of token 16*pg + 4*(lane/16) + r for query row lane%16
-            f32x4 s[RBW][2];
+    auto compute = [&](int ti, const unsigned char *cur) {
+        const int tile_tok0 = tok_begin + ti * DAS_ATTN_TILE;
+        // S^T = K Q^T : s[i][pg][r] = score of token 16*pg + 4*(lane/16) + r for query row lane%16
+        f32x4 s[RBW][2];
 #pragma unroll
-            for (int i = 0; i < RBW; ++i) { s[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+        for (int i = 0; i < RBW; ++i) { s[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-            for (int ks = 0; ks < KFR; ++ks) {
-                const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(cur + (ks * 64 + lane) * 16);
-                const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
-#pragma unroll
-                for (int i = 0; i < RBW; ++i) {
-                    s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s[i][0], 0, 0, 0);
-                    s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s[i][1], 0, 0, 0);
-                }
-            }
-            const bool need_mask = tile_tok0 + DAS_ATTN_TILE - 1 > ctx;
-            bf16x8 pf[RBW];
+        for (int ks = 0; ks < KFR; ++ks) {
+            const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(cur + (ks * 64 + lane) * 16);
+            const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
 #pragma unroll
             for (int i = 0; i < RBW; ++i) {
-                float sv[8];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) { sv[r] = s[i][0][r] * scale_log2e; sv[4 + r] = s[i][1][r] * scale_log2e; }
-                if (need_mask) {
-                    const int pbase = tile_tok0 + 4 * (lane >> 4);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if (pbase + r > lim[i]) sv[r] = -INFINITY;
-                        if (pbase + 16 + r > lim[i]) sv[4 + r] = -INFINITY;
-                    }
-                }
-                float mt = sv[0];
-#pragma unroll
-                for (int r = 1; r < 8; ++r) mt = fmaxf(mt, sv[r]);
-                mt = fmaxf(mt, __shfl_xor(mt, 16));
-                mt = fmaxf(mt, __shfl_xor(mt, 32));
-                const float mn = fmaxf(m_run[i], mt);
-                const float ms = (mn == -INFINITY) ? 0.f : mn;
-                const float alpha = exp2f(m_run[i] - ms);
-                float ps = 0.f;
-                float pv[8];
-#pragma unroll
-                for (int r = 0; r < 8; ++r) { pv[r] = exp2f(sv[r] - ms); ps += pv[r]; }
-                l_run[i] = l_run[i] * alpha + ps;
-                m_run[i] = mn;
-#pragma unroll
-                for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
-#pragma unroll
-                for (int r = 0; r < 8; ++r) pf[i][r] = (__bf16)pv[r];
-            }
-            // O^T += V^T P^T : A = V fragment (dims x 32 token slots), B = probabilities
-#pragma unroll
-            for (int db = 0; db < VDB; ++db) {
-                const uint2 lo = *reinterpret_cast<const uint2 *>(cur + 2 * PAGE_B + (db * 64 + lane) * 8);
-                const uint2 hi = *reinterpret_cast<const uint2 *>(cur + 3 * PAGE_B + (db * 64 + lane) * 8);
-                uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
-#pragma unroll
-                for (int i = 0; i < RBW; ++i)
-                    acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[i], acc[i][db], 0, 0, 0);
+                s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s[i][0], 0, 0, 0);
+                s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s[i][1], 0, 0, 0);
             }
         }
-        if (ti + 1 < ntiles) store_tile((ti + 1) & 1);
-        __syncthreads();
+        const bool need_mask = tile_tok0 + DAS_ATTN_TILE - 1 > ctx;
+        bf16x8 pf[RBW];
+#pragma unroll
+        for (int i = 0; i < RBW; ++i) {
+            float sv[8];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { sv[r] = s[i][0][r] * scale_log2e; sv[4 + r] = s[i][1][r] * scale_log2e; }
+            if (need_mask) {
+                const int pbase = tile_tok0 + 4 * (lane >> 4);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (pbase + r > lim[i]) sv[r] = -INFINITY;
+                    if (pbase + 16 + r > lim[i]) sv[4 + r] = -INFINITY;
+                }
+            }
+            float mt = sv[0];
+#pragma unroll
+            for (int r = 1; r < 8; ++r) mt = fmaxf(mt, sv[r]);
+            mt = fmaxf(mt, __shfl_xor(mt, 16));
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            const float mn = fmaxf(m_run[i], mt);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            const float alpha = exp2f(m_run[i] - ms);
+            float ps = 0.f;
+            float pv[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) { pv[r] = exp2f(sv[r] - ms); ps += pv[r]; }
+            l_run[i] = l_run[i] * alpha + ps;
+            m_run[i] = mn;
+#pragma unroll
+            for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) pf[i][r] = (__bf16)pv[r];
+        }
+        // O^T += V^T P^T : A = V fragment (dims x 32 token slots), B = probabilities
+#pragma unroll
+        for (int db = 0; db < VDB; ++db) {
+            const uint2 lo = *reinterpret_cast<const uint2 *>(cur + 2 * PAGE_B + (db * 64 + lane) * 8);
+            const uint2 hi = *reinterpret_cast<const uint2 *>(cur + 3 * PAGE_B + (db * 64 + lane) * 8);
+            uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
+#pragma unroll
+            for (int i = 0; i < RBW; ++i)
+                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[i], acc[i][db], 0, 0, 0);
+        }
+    };
+
+    // Tile ti lives in stage ti % 3.  At the top of a section the copies of tile ti have landed for
+    // every wave (at most the newer tile's NLOAD copies are still in flight) and every wave is done
+    // with tile ti-1, whose stage is then refilled with tile ti+2.  Copies are issued unconditionally
+    // (past the end: the last tile again, into a stage nobody reads) so that the wait is the same
+    // straight-line s_waitcnt in every section; the leftovers are drained before the epilogue.
+    auto landed = [&]() {
+        // s_waitcnt immediate: vmcnt in bits 3:0; expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
+        if (NLOAD == 4) __builtin_amdgcn_s_waitcnt(0xF74); else __builtin_amdgcn_s_waitcnt(0xF72);
+        __builtin_amdgcn_s_barrier();      // bare barrier: a fence here would drain the copies in flight
+    };
+    const int last = ntiles - 1;
+    issue(0, st0);
+    issue(min(1, last), st1);
+    landed();                               // first tile peeled: the loop is entered in its steady state
+    issue(min(2, last), st2);
+    if (any_active) compute(0, st0);
+    for (int ti = 1; ti < ntiles; ti += 3) {
+        landed();
+        issue(min(ti + 2, last), st0);
+        if (any_active) compute(ti, st1);
+        if (ti + 1 >= ntiles) break;
+        landed();
+        issue(min(ti + 3, last), st1);
+        if (any_active) compute(ti + 1, st2);
+        if (ti + 2 >= ntiles) break;
+        landed();
+        issue(min(ti + 4, last), st2);
+        if (any_active) compute(ti + 2, st0);
     }
+    __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
     // ---- partial results: (m, l) per row and the un-normalised accumulator
 #pragma unroll
@@ -195,7 +222,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     if (n_items <= 0) return;
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
     dim3 g(n_items, dm.Hkv), blk(256);
-    const size_t lds = 2 * 4 * (size_t)(DAS_PAGE * dm.D * 2);
+    const size_t lds = 0;     // tile stages are static LDS arrays
 #define ATTN_LAUNCH(DD, RB) \
     attn_partial_kernel<DD, RB><<<g, blk, lds, st>>>(pm, items, qkv, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.qkvN, sc)
     if (dm.D == 128) {
