@@ -96,6 +96,11 @@ class Rollout:
         log(f"[bench] {self.horizon} plain decode steps for the drafter in {time.time() - t0:.1f}s "
             f"({(time.time() - t0) / self.horizon * 1e3:.2f} ms/step)")
 
+    def random_proposals(self):
+        rng = np.random.default_rng(self.seed + 31)
+        self.proposal = rng.integers(0, self.shape.vocab, size=(self.B, self.horizon + 1), dtype=np.int32)
+        self.emitted = np.ones(self.B, np.int64)
+
     def step(self, sampling=None):
         ks = di.draft_budgets(self.wl, self.ctx)
         drafts = [self.proposal[i, self.emitted[i]:self.emitted[i] + ks[i]] for i in range(self.B)]
@@ -140,6 +145,20 @@ def kernel_rooflines(shape, prof, T, kv_tokens, n_steps):
         e["frac"] = e["achieved"] / e["peak"]
         out[name] = e
     return out
+
+
+def stored_traffic(workload, kernel_class):
+    """HBM-side bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by the plain copy kernel), if one exists for this workload and kernel class; else None."""
+    path = os.path.join(ROOT, "profiles", f"verify_step_{workload}_traffic.json")
+    prefix = {"attention": "void attn_partial_kernel", "gemm_gateup_silu": "void gemm_kernel<2, 2, 2, 2, 2>",
+              "gemm_qkv": "void gemm_kernel<2, 2, 2, 2, 0>", "gemm_lm_head": "void gemm_kernel<2, 2, 2, 2, 3>",
+              "attention_merge": "void attn_merge_kernel"}.get(kernel_class)
+    if not prefix or not os.path.exists(path):
+        return None
+    per = json.load(open(path))["per_launch"]
+    hits = [v for k, v in per.items() if k.startswith(prefix)]
+    return sum(v["fetch_bytes"] + v["write_bytes"] for v in hits) if hits else None
 
 
 def cpu_baseline(ro, budget_s=20.0):
@@ -192,6 +211,10 @@ def main():
     ap.add_argument("--context", default="synth", choices=["synth", "prefill"])
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--drafts", default="trajectory", choices=["trajectory", "random"],
+                    help="random: uniform random drafts, no plain-decoding pass (same kernel shapes; for profiler runs)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also launch a plain copy kernel of this size 3 times (profiler byte-counter reference)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     args = ap.parse_args()
@@ -204,7 +227,10 @@ def main():
     wl = di.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
     ro = Rollout(wl, batch=args.batch, n_layers=args.layers, context=args.context, max_steps=W + 2 * K + 1)
-    ro.generate_trajectories()
+    if args.drafts == "trajectory":
+        ro.generate_trajectories()
+    else:
+        ro.random_proposals()
 
     for _ in range(W):
         ro.step()
@@ -235,12 +261,16 @@ def main():
         cand = {k: v for k, v in kernels.items() if "frac" in v}
         dom = max(cand, key=lambda k: cand[k]["ms_per_step"])
         e = cand[dom]
-        roof = {"kernel": dom, "bound": e["bound"], "achieved": e["achieved"], "peak": e["peak"], "unit": e["unit"],
-                "frac": e["frac"], "traffic": None, "ms_per_launch": e["ms_per_launch"],
+        e["algorithmic"] = e["achieved"] * e["ms_per_launch"] * (1e9 if e["unit"] == "TFLOP/s" else 1e6)
+        roof = {"kernel": dom, "algorithmic_per_launch": e["algorithmic"], "bound": e["bound"], "achieved": e["achieved"], "peak": e["peak"], "unit": e["unit"],
+                "frac": e["frac"], "traffic": stored_traffic(wl.name, dom), "ms_per_launch": e["ms_per_launch"],
                 "share_of_step": e["ms_per_step"] / sum(v["ms_per_step"] for v in kernels.values())}
 
+    if args.calibrate_copy:
+        ro.das.debug_copy(args.calibrate_copy << 20, 3)
+
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.drafts == "trajectory":
         cpu = cpu_baseline(ro)
 
     out = {

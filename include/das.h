@@ -146,6 +146,10 @@ int das_debug_free_pages(das_model *m, int64_t *n_free);
  * a and w row-major bf16, K a multiple of 8.  Needs no model. */
 int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c);
 
+/* Device-to-device copy of `bytes` (multiple of 16) by a trivial kernel, `repeats` times: a dispatch of
+ * known HBM traffic (bytes read + bytes written) against which profiler byte counters are scaled. */
+int das_debug_copy(int64_t bytes, int32_t repeats);
+
 /* ---- per-kernel timing with HIP events on the library's own stream ---- */
 #define DAS_NUM_KERNEL_CLASSES 16
 int das_profile_enable(das_model *m, int32_t on);          /* on: every launch is bracketed by events */

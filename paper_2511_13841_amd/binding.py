@@ -60,6 +60,7 @@ def lib():
             "das_debug_seq": [P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I), VP, C.POINTER(I)],
             "das_debug_free_pages": [P, C.POINTER(C.c_int64)],
             "das_debug_gemm": [I, I, I, VP, VP, VP],
+            "das_debug_copy": [C.c_int64, I],
             "das_profile_enable": [P, I],
             "das_profile_reset": [P],
             "das_profile_read": [P, I, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
@@ -113,6 +114,10 @@ def debug_gemm(a_bf16, w_bf16):
     c = np.empty((M, N), np.float32)
     _chk(lib().das_debug_gemm(M, N, K, a.ctypes.data, w.ctypes.data, c.ctypes.data), "das_debug_gemm")
     return c
+
+
+def debug_copy(nbytes, repeats=1):
+    _chk(lib().das_debug_copy(int(nbytes), int(repeats)), "das_debug_copy")
 
 
 class DasModel:

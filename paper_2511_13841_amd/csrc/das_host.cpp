@@ -820,6 +820,21 @@ extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a
     return rc;
 }
 
+// Plain device-to-device copy of `bytes` (multiple of 16) with a trivial kernel: the known-traffic
+// reference that scales the profiler's HBM byte counters.
+extern "C" int das_debug_copy(int64_t bytes, int32_t repeats) {
+    if (bytes < 16 || (bytes % 16) || repeats < 1) return DAS_ERR_INVALID;
+    void *a = nullptr, *b = nullptr;
+    if (hipMalloc(&a, (size_t)bytes) != hipSuccess) { (void)hipGetLastError(); return DAS_ERR_NOMEM; }
+    if (hipMalloc(&b, (size_t)bytes) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(a); return DAS_ERR_NOMEM; }
+    int rc = DAS_OK;
+    if (hipMemset(a, 1, (size_t)bytes) != hipSuccess) rc = DAS_ERR_DEVICE;
+    for (int r = 0; r < repeats && rc == DAS_OK; ++r) launch_copy(a, b, (size_t)bytes, nullptr);
+    if (hipDeviceSynchronize() != hipSuccess) rc = DAS_ERR_DEVICE;
+    (void)hipFree(a); (void)hipFree(b);
+    return rc;
+}
+
 // ------------------------------------------------------------------------------------------------ profiling / errors
 
 extern "C" int das_profile_enable(das_model *m, int32_t on) {

@@ -101,3 +101,4 @@ void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_
                   bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, hipStream_t st);
 void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D,
                      uint64_t seed, uint64_t seq_key, int layer, hipStream_t st);
+void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st);

@@ -1,6 +1,7 @@
 // Element-wise and data-movement kernels of the verify step: weight repacking,
 // embedding gather, RMSNorm, RoPE + paged KV write, KV import/export.
 #include "das_internal.h"
+#include <algorithm>
 
 __device__ __forceinline__ float bf2f(bf16_t x) { return __uint_as_float((uint32_t)x << 16); }
 __device__ __forceinline__ bf16_t f2bf(float f) {
@@ -227,4 +228,16 @@ void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *
     uint64_t b = host_mix64(host_mix64(seed ^ 0x4B5653594E544821ull) ^ seq_key);
     uint64_t bk = host_mix64(b ^ ((uint64_t)layer * 2u)), bv = host_mix64(b ^ ((uint64_t)layer * 2u + 1u));
     kv_synth_kernel<<<dim3(ctx, Hkv), dim3(D), 0, st>>>(page_row, kpool_layer, vpool_layer, Hkv, D, bk, bv);
+}
+
+// ---------------------------------------------------------------- plain copy (counter calibration)
+__global__ void plain_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
+    const size_t n = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 32);
+    plain_copy_kernel<<<dim3(grid), dim3(256), 0, st>>>(reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint4 *>(dst), n);
 }
