@@ -7,6 +7,7 @@
 // v_mfma_f32_32x32x16_bf16; the K loop of every output element runs in the same
 // order whatever M is, so a row's result does not depend on the batch around it.
 #include "das_internal.h"
+#include <cstdlib>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -17,16 +18,18 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
     return (bf16_t)(u >> 16);
 }
 
-// 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at lds + 16*l.
-__device__ __forceinline__ void dma16(const void *g, void *lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+// 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at
+// lds_wave_base + 16*l.  Issued as inline assembly so that the copies are ordered only by the explicit
+// s_waitcnt/s_barrier below: the compiler's own bookkeeping would drain every copy in flight before
+// the first LDS read after a loop header.  M0 carries the LDS address (1 wait state before its use).
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
 
-// WGM x WGN waves, each owning TM x TN blocks of 32x32.  BK = 64 (4 MFMA k-steps).
-// Two k-tile stages live in two separate LDS arrays so that the compiler can tell the stage being
-// filled by the DMA from the stage being read, and lets the copy run under the MFMAs.
-template <int WGM, int WGN, int TM, int TN, int EPI>
+// WGM x WGN waves, each owning TM x TN blocks of 32x32.  BK = 64 (4 MFMA k-steps).  NS LDS stages form a
+// ring: while k-tile kt is multiplied, k-tiles kt+1 .. kt+NS-2 are already in flight and the stage of
+// kt-1 is being refilled with kt+NS-1.
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
                                                              int tiles_m, int tiles_n) {
@@ -36,9 +39,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     constexpr int NLOAD = (A_UNITS + B_UNITS) / NT;
     static_assert((A_UNITS + B_UNITS) % NT == 0, "tile must divide evenly over the threads");
     static_assert(A_UNITS % NT == 0, "A/W split must fall on a whole pass over the threads");
+    static_assert((NS - 2) * NLOAD <= 63, "vmcnt is a 6-bit counter");
     constexpr int STAGE_BYTES = (AB + BB) * 4096;
-    __shared__ __align__(16) unsigned char stage0[STAGE_BYTES];
-    __shared__ __align__(16) unsigned char stage1[STAGE_BYTES];
+    extern __shared__ __align__(16) unsigned char smem[];
 
     // XCD-aware tile order: the workgroups of one XCD (id % 8) walk a contiguous
     // run of tiles, M fastest, so tiles sharing a weight tile share an L2.
@@ -54,6 +57,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int KT = K >> 6;                                 // k-tiles
     const uint4 *Ag = reinterpret_cast<const uint4 *>(A);
     const uint4 *Wg = reinterpret_cast<const uint4 *>(W);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem + wave * 1024;
 
     // per-thread source of each 16-byte unit u = tid + j*NT: units below A_UNITS come from A, the rest from W
     const uint4 *src[NLOAD];
@@ -72,45 +76,53 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    auto issue = [&](int kt, unsigned char *stage) {       // 4 fragments = 256 uint4 per k-tile and row block
+    auto issue = [&](int kt, int stage) {                  // 4 fragments = 256 uint4 per k-tile and row block
 #pragma unroll
-        for (int j = 0; j < NLOAD; ++j) dma16(src[j] + (size_t)kt * 256, stage + j * NT * 16 + wave * 1024);
+        for (int j = 0; j < NLOAD; ++j) dma16(src[j] + (size_t)kt * 256, lds_base + stage * STAGE_BYTES + j * NT * 16);
     };
     auto compute = [&](const unsigned char *cur) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 a[TM], b[TN];
+        // fragments of k-step ks+1 are requested before the MFMAs of k-step ks are issued
+        bf16x8 a[2][TM], b[2][TN];
+        auto fetch = [&](int ks, int buf) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                a[i] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + i) * 4 + ks) * 1024 + lane * 16);
+                a[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + i) * 4 + ks) * 1024 + lane * 16);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                b[j] = *reinterpret_cast<const bf16x8 *>(cur + AB * 4096 + ((wn * TN + j) * 4 + ks) * 1024 + lane * 16);
+                b[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + AB * 4096 + ((wn * TN + j) * 4 + ks) * 1024 + lane * 16);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) fetch(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (EPI == EPI_SILU_FRAG)   // transposed block: rows = weight rows, cols = activation rows
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
                     else
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
                 }
         }
     };
-    auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); };
 
-    issue(0, stage0);
-    landed();
-    for (int kt = 0;; kt += 2) {                           // even k-tiles in stage0, odd ones in stage1
-        if (kt + 1 < KT) issue(kt + 1, stage1);
-        compute(stage0);
-        if (kt + 1 >= KT) break;
-        landed();
-        if (kt + 2 < KT) issue(kt + 2, stage0);
-        compute(stage1);
-        if (kt + 2 >= KT) break;
-        landed();
+    // Copies are issued unconditionally (past the end: the last k-tile again, into a stage nobody will read),
+    // so "all but the newest NS-2 tiles have landed" is the same s_waitcnt in every iteration.
+    const int last = KT - 1;
+#pragma unroll
+    for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(s0, last), s0);
+    int stage = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD & 15) | (((NS - 2) * NLOAD >> 4) << 14));   // vmcnt only
+        __builtin_amdgcn_s_barrier();      // tile kt visible to all waves; all waves are done with tile kt-1
+        asm volatile("" ::: "memory");
+        const int refill = stage == 0 ? NS - 1 : stage - 1;
+        issue(min(kt + NS - 1, last), refill);
+        compute(smem + stage * STAGE_BYTES);
+        stage = stage == NS - 1 ? 0 : stage + 1;
     }
+    __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
     const int m0 = tile_m * AB * 32 + wm * TM * 32, n0 = tile_n * BB * 32 + wn * TN * 32;
     const int lr = lane & 31, lh = lane >> 5;
@@ -158,23 +170,29 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     }
 }
 
-template <int WGM, int WGN, int TM, int TN>
-static void launch_cfg(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
+static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int LDS = NS * (WGM * TM + WGN * TN) * 4096;
+    static_assert(LDS <= 160 * 1024, "LDS of one CU");
+    static bool configured = false;
+    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI>;
+    if (!configured) {      // dynamic LDS above the default limit has to be granted once per kernel
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        configured = true;
+    }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int nt = tiles_m * tiles_n;
-    const int grid = ((nt + 7) / 8) * 8;
-    const size_t lds = 0;     // the two k-tile stages are static LDS arrays
-    dim3 g(grid), b(WGM * WGN * 64);
+    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n);
+}
+
+template <int WGM, int WGN, int TM, int TN, int NS>
+static void launch_cfg(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
     switch (epi) {
-    case EPI_BF16_ROWMAJOR:
-        gemm_kernel<WGM, WGN, TM, TN, EPI_BF16_ROWMAJOR><<<g, b, lds, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n); break;
-    case EPI_RESID_F32:
-        gemm_kernel<WGM, WGN, TM, TN, EPI_RESID_F32><<<g, b, lds, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n); break;
-    case EPI_SILU_FRAG:
-        gemm_kernel<WGM, WGN, TM, TN, EPI_SILU_FRAG><<<g, b, lds, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n); break;
-    default:
-        gemm_kernel<WGM, WGN, TM, TN, EPI_F32_ROWMAJOR><<<g, b, lds, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n); break;
+    case EPI_BF16_ROWMAJOR: launch_one<WGM, WGN, TM, TN, NS, EPI_BF16_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
+    case EPI_RESID_F32: launch_one<WGM, WGN, TM, TN, NS, EPI_RESID_F32>(A, W, C, M, N, K, ldc, st); break;
+    case EPI_SILU_FRAG: launch_one<WGM, WGN, TM, TN, NS, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st); break;
+    default: launch_one<WGM, WGN, TM, TN, NS, EPI_F32_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
     }
 }
 
@@ -182,5 +200,13 @@ static void launch_cfg(int epi, const bf16_t *A, const bf16_t *W, void *C, int M
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
     if (M <= 0) return;
-    launch_cfg<2, 2, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
+    // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
+    //  * wide outputs (gate/up, LM head): 256x256, 8 waves (2 x 4) of 128x64 -- half the bytes per flop of a
+    //    128x128 tile through the HBM->LDS copy path, which is what saturates first;
+    //  * narrow outputs (QKV, O, down; N of a few thousand): 128x128 with 8 waves and a 4-stage ring so that the
+    //    one workgroup a CU gets covers the copy latency by itself;
+    //  * few rows (T <= 512: weight streaming): 128x64 tiles, 5 stages, twice as many workgroups.
+    if (M > 256 && N >= 16384) launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
+    else if (M > 512) launch_cfg<2, 4, 2, 1, 4>(epi, A, W, C, M, N, K, ldc, st);
+    else launch_cfg<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
 }
