@@ -40,6 +40,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     static_assert((A_UNITS + B_UNITS) % NT == 0, "tile must divide evenly over the threads");
     static_assert(A_UNITS % NT == 0, "A/W split must fall on a whole pass over the threads");
     static_assert((NS - 2) * NLOAD <= 63, "vmcnt is a 6-bit counter");
+    static_assert(EPI != EPI_SILU_FRAG || TN % 2 == 0, "gate and up blocks must sit in the same wave");
     constexpr int STAGE_BYTES = (AB + BB) * 4096;
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -196,6 +197,16 @@ static void launch_cfg(int epi, const bf16_t *A, const bf16_t *W, void *C, int M
     }
 }
 
+// the three epilogues that any wave layout supports
+template <int WGM, int WGN, int TM, int TN, int NS>
+static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
+    switch (epi) {
+    case EPI_BF16_ROWMAJOR: launch_one<WGM, WGN, TM, TN, NS, EPI_BF16_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
+    case EPI_RESID_F32: launch_one<WGM, WGN, TM, TN, NS, EPI_RESID_F32>(A, W, C, M, N, K, ldc, st); break;
+    default: launch_one<WGM, WGN, TM, TN, NS, EPI_F32_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
+    }
+}
+
 // A must be allocated for M rounded up to 256 rows, W for N rounded up to 256 rows; K % 64 == 0.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
@@ -206,7 +217,11 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     //  * narrow outputs (QKV, O, down; N of a few thousand): 128x128 with 8 waves and a 4-stage ring so that the
     //    one workgroup a CU gets covers the copy latency by itself;
     //  * few rows (T <= 512: weight streaming): 128x64 tiles, 5 stages, twice as many workgroups.
+    // The SiLU epilogue pairs a gate block with the up block next to it, so its waves own two column blocks.
     if (M > 256 && N >= 16384) launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
-    else if (M > 512) launch_cfg<2, 4, 2, 1, 4>(epi, A, W, C, M, N, K, ldc, st);
-    else launch_cfg<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
+    else if (epi == EPI_SILU_FRAG) {
+        if (M > 512) launch_one<4, 2, 1, 2, 4, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
+        else launch_one<4, 1, 1, 2, 5, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
+    } else if (M > 512) launch_cfg3<2, 4, 2, 1, 4>(epi, A, W, C, M, N, K, ldc, st);
+    else launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
 }
