@@ -21,11 +21,14 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-// 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at lds + 16*l.
-__device__ __forceinline__ void dma16(const void *g, void *lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+// 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at
+// lds_wave_base + 16*l.  Inline assembly, so that the copies are ordered only by the explicit
+// s_waitcnt/s_barrier of the tile loop (M0 carries the LDS address; 1 wait state before its use).
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
+
+#define DAS_ATTN_STAGES 4
 
 template <int D, int RBW>
 __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
@@ -41,10 +44,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
     constexpr int TILE_B = 4 * PAGE_B;     // K page0, K page1, V page0, V page1
     constexpr int UNITS_PER_SEG = PAGE_B / 16;
     constexpr int NLOAD = (TILE_B / 16) / 256;
-    // three tile stages in three separate LDS arrays: one being read, two being filled by the DMA
-    __shared__ __align__(16) unsigned char st0[TILE_B];
-    __shared__ __align__(16) unsigned char st1[TILE_B];
-    __shared__ __align__(16) unsigned char st2[TILE_B];
+    constexpr int NS = DAS_ATTN_STAGES;    // ring of tile stages: one being read, NS-1 being filled
+    __shared__ __align__(16) unsigned char smem[NS * TILE_B];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
     const int b = items[2 * blockIdx.x], chunk = items[2 * blockIdx.x + 1];
     const int kvh = blockIdx.y;
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
     }
 
     // ---- tile loader: 16-byte unit u of the tile belongs to segment u / UNITS_PER_SEG
-    auto issue = [&](int ti, unsigned char *stage) {
+    auto issue = [&](int ti, int stage) {
         const int pg0 = __builtin_amdgcn_readlane(my_page, 2 * ti);
         const int pg1 = __builtin_amdgcn_readlane(my_page, 2 * ti + 1);     // clamped to the last page at load
 #pragma unroll
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
             const int seg = u / UNITS_PER_SEG, off = u % UNITS_PER_SEG;
             const int pg = (seg & 1) ? pg1 : pg0;
             const bf16_t *base = (seg < 2 ? kpool : vpool) + ((size_t)pg * Hkv + kvh) * PAGE_E;
-            dma16(reinterpret_cast<const uint4 *>(base) + off, stage + jn * 4096 + wave * 1024);
+            dma16(reinterpret_cast<const uint4 *>(base) + off, lds_base + stage * TILE_B + jn * 4096 + wave * 1024);
         }
     };
 
@@ -124,6 +126,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
         bf16x8 pf[RBW];
 #pragma unroll
         for (int i = 0; i < RBW; ++i) {
+            // Softmax with a lazily updated reference: p = exp2(s - m_ref).  m_ref only moves when the row's
+            // maximum in this tile exceeds it by more than 8 (a factor 256), which after a row's first tile
+            // almost never happens: the common path needs no cross-lane step and no rescaling of the
+            // accumulators.  The decision is taken per ROW (from the row's own maximum), so a row's
+            // arithmetic never depends on its neighbours; softmax is shift-invariant, the result is exact.
             float sv[8];
 #pragma unroll
             for (int r = 0; r < 4; ++r) { sv[r] = s[i][0][r] * scale_log2e; sv[4 + r] = s[i][1][r] * scale_log2e; }
@@ -138,19 +145,22 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
             float mt = sv[0];
 #pragma unroll
             for (int r = 1; r < 8; ++r) mt = fmaxf(mt, sv[r]);
-            mt = fmaxf(mt, __shfl_xor(mt, 16));
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float mn = fmaxf(m_run[i], mt);
-            const float ms = (mn == -INFINITY) ? 0.f : mn;
-            const float alpha = exp2f(m_run[i] - ms);
+            if (__any(mt > m_run[i] + 8.f)) {          // some row of this block may have to move its reference
+                mt = fmaxf(mt, __shfl_xor(mt, 16));
+                mt = fmaxf(mt, __shfl_xor(mt, 32));    // the row's maximum, same in its four lanes
+                const float mn = (mt > m_run[i] + 8.f) ? mt : m_run[i];
+                const float alpha = exp2f(m_run[i] - ((mn == -INFINITY) ? 0.f : mn));   // 1 for rows that stay
+                l_run[i] *= alpha;
+                m_run[i] = mn;
+#pragma unroll
+                for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
+            }
+            const float ms = (m_run[i] == -INFINITY) ? 0.f : m_run[i];
             float ps = 0.f;
             float pv[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) { pv[r] = exp2f(sv[r] - ms); ps += pv[r]; }
-            l_run[i] = l_run[i] * alpha + ps;
-            m_run[i] = mn;
-#pragma unroll
-            for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
+            for (int r = 0; r < 8; ++r) { pv[r] = __builtin_amdgcn_exp2f(sv[r] - ms); ps += pv[r]; }
+            l_run[i] += ps;
 #pragma unroll
             for (int r = 0; r < 8; ++r) pf[i][r] = (__bf16)pv[r];
         }
@@ -167,34 +177,21 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
         }
     };
 
-    // Tile ti lives in stage ti % 3.  At the top of a section the copies of tile ti have landed for
-    // every wave (at most the newer tile's NLOAD copies are still in flight) and every wave is done
-    // with tile ti-1, whose stage is then refilled with tile ti+2.  Copies are issued unconditionally
-    // (past the end: the last tile again, into a stage nobody reads) so that the wait is the same
-    // straight-line s_waitcnt in every section; the leftovers are drained before the epilogue.
-    auto landed = [&]() {
-        // s_waitcnt immediate: vmcnt in bits 3:0; expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
-        if (NLOAD == 4) __builtin_amdgcn_s_waitcnt(0xF74); else __builtin_amdgcn_s_waitcnt(0xF72);
-        __builtin_amdgcn_s_barrier();      // bare barrier: a fence here would drain the copies in flight
-    };
+    // Tile ti lives in stage ti % NS.  At the top of an iteration the copies of tile ti have landed for
+    // every wave (only the NS-2 newer tiles may still be in flight) and every wave is done with tile
+    // ti-1, whose stage is then refilled with tile ti+NS-1.  Copies are issued unconditionally (past the
+    // end: the last tile again, into a stage nobody reads) so that the wait is the same in every iteration.
     const int last = ntiles - 1;
-    issue(0, st0);
-    issue(min(1, last), st1);
-    landed();                               // first tile peeled: the loop is entered in its steady state
-    issue(min(2, last), st2);
-    if (any_active) compute(0, st0);
-    for (int ti = 1; ti < ntiles; ti += 3) {
-        landed();
-        issue(min(ti + 2, last), st0);
-        if (any_active) compute(ti, st1);
-        if (ti + 1 >= ntiles) break;
-        landed();
-        issue(min(ti + 3, last), st1);
-        if (any_active) compute(ti + 1, st2);
-        if (ti + 2 >= ntiles) break;
-        landed();
-        issue(min(ti + 4, last), st2);
-        if (any_active) compute(ti + 2, st0);
+#pragma unroll
+    for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(s0, last), s0);
+    int stage = 0;
+    for (int ti = 0; ti < ntiles; ++ti) {
+        __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD));       // vmcnt only (expcnt, lgkmcnt: no wait)
+        __builtin_amdgcn_s_barrier();      // bare barrier: a fence here would drain the copies in flight
+        asm volatile("" ::: "memory");
+        issue(min(ti + NS - 1, last), stage == 0 ? NS - 1 : stage - 1);
+        if (any_active) compute(ti, smem + stage * TILE_B);
+        stage = stage == NS - 1 ? 0 : stage + 1;
     }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
