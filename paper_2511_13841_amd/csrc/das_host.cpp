@@ -218,7 +218,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     pm.tok = dptr(tok); pm.row_pos = dptr(row_pos); pm.row_b = dptr(row_b); pm.sel = dptr(sel); pm.n_sel = n_sel;
     pm.b_slot = dptr(b_slot); pm.b_start = dptr(b_start); pm.b_n = dptr(b_n); pm.b_row0 = dptr(b_row0);
     pm.b_prow = dptr(b_prow); pm.b_nchunk = dptr(b_nchunk);
-    pm.page_table = m->page_table; pm.max_pages = m->max_pages;
+    pm.page_table = m->page_table; pm.max_pages = m->max_pages; pm.num_pages = (int)m->cfg.num_pages;
     {
         ProfScope ps(m, KC_META);
         HIPCHK(hipMemcpyAsync(m->d_stage, m->h_stage, used * sizeof(int), hipMemcpyHostToDevice, st));
@@ -718,7 +718,7 @@ static int kv_io(das_model *m, int mode, int32_t seq_id, int32_t layer, int32_t 
             if (fail(hipMemcpy(dk, k, cnt * 2, hipMemcpyHostToDevice))) break;
             if (fail(hipMemcpy(dv, v, cnt * 2, hipMemcpyHostToDevice))) break;
         }
-        { ProfScope ps(m, KC_KVIO); launch_kv_io(mode, prow, first_pos, n_pos, kl, vl, dk, dv, m->dm.Hkv, m->dm.D, m->st); }
+        { ProfScope ps(m, KC_KVIO); launch_kv_io(mode, prow, first_pos, n_pos, kl, vl, dk, dv, m->dm.Hkv, m->dm.D, (int)m->cfg.num_pages, m->st); }
         if (fail(hipStreamSynchronize(m->st))) break;
         if (mode == 1) {
             if (fail(hipMemcpy(k, dk, cnt * 2, hipMemcpyDeviceToHost))) break;
@@ -750,7 +750,7 @@ extern "C" int das_kv_synth(das_model *m, int32_t seq_id, uint64_t seed, uint64_
         ProfScope ps(m, KC_KVIO);
         for (int l = 0; l < m->dm.L; ++l)
             launch_kv_synth(prow, s.ctx, m->kpool + (size_t)l * m->layer_elems, m->vpool + (size_t)l * m->layer_elems,
-                            m->dm.Hkv, m->dm.D, seed, seq_key, l, m->st);
+                            m->dm.Hkv, m->dm.D, (int)m->cfg.num_pages, seed, seq_key, l, m->st);
     }
     HIPCHK(hipStreamSynchronize(m->st));
     prof_collect(m);

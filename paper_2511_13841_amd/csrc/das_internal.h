@@ -9,7 +9,8 @@
 //    in ks.  A wave fetches an operand with one fully coalesced 16-byte load
 //    per lane and no shuffling; tiles copy to LDS linearly and are read back
 //    with conflict-free ds_read_b128.
-//  * The KV cache is paged (16 tokens).  A K page of one KV head is stored as
+//  * The KV cache is paged (16 tokens); one layer is [page][H_kv][16*D] (measured faster than head-major:
+//    the four heads' workgroups of a chunk then stream one contiguous region together).  A K page of one KV head is stored as
 //    the A operand of v_mfma_f32_16x16x32_bf16 (16 tokens x 32 dims per
 //    fragment, D/32 fragments); a V page as [D/16 dim blocks][4 token
 //    groups][16 dims][4 tokens] so that a lane's 8-byte load from each of two
@@ -68,6 +69,7 @@ struct PassMeta {
     int n_sel;
     const int *page_table; // [max_seqs][max_pages]
     int max_pages;
+    int num_pages;         // pages in the pool
 };
 
 enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3 };
@@ -98,7 +100,7 @@ void launch_sample(const float *logits, int V, const int *tok, const int *b_row0
                    float inv_temp, const float *u_accept, const float *u_sample, int prefill_mode,
                    float *row_stats, int *accept_len, int *next_token, hipStream_t st);
 void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_t *kpool_layer, bf16_t *vpool_layer,
-                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, hipStream_t st);
-void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D,
+                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, hipStream_t st);
+void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D, int num_pages,
                      uint64_t seed, uint64_t seq_key, int layer, hipStream_t st);
 void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st);

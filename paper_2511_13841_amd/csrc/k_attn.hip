@@ -28,10 +28,11 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
 
-#define DAS_ATTN_STAGES 4
-
-template <int D, int RBW>
-__global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
+// Two waves per SIMD are asked for whenever the row blocks fit 256 registers: besides the occupancy, it
+// makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
+// without copies out of the accumulation register file on every tile.
+template <int D, int RBW, int NS, int MINW>
+__global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const bf16_t *__restrict__ qkv,
                                                            const bf16_t *__restrict__ kpool,
                                                            const bf16_t *__restrict__ vpool,
@@ -44,10 +45,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
     constexpr int TILE_B = 4 * PAGE_B;     // K page0, K page1, V page0, V page1
     constexpr int UNITS_PER_SEG = PAGE_B / 16;
     constexpr int NLOAD = (TILE_B / 16) / 256;
-    constexpr int NS = DAS_ATTN_STAGES;    // ring of tile stages: one being read, NS-1 being filled
+    // ring of NS tile stages: one being read, NS-1 being filled
     __shared__ __align__(16) unsigned char smem[NS * TILE_B];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
+    // items fastest in dispatch order (measured faster than running a chunk's KV heads side by side)
     const int b = items[2 * blockIdx.x], chunk = items[2 * blockIdx.x + 1];
     const int kvh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -62,7 +64,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
     // the chunk's (at most 64) page ids, one per lane, fetched once: the tile loop then takes them with
     // v_readlane and never waits on a vector load of its own (which would also wait for every copy in flight)
     const int first_page = tok_begin >> 4;
-    const int my_page = pt[min(first_page + lane, npages - 1)];
+    constexpr int NPREG = DAS_ATTN_CHUNK / DAS_PAGE / 64;      // registers of 64 page ids each
+    int my_page[NPREG];
+#pragma unroll
+    for (int q = 0; q < NPREG; ++q) my_page[q] = pt[min(first_page + q * 64 + lane, npages - 1)];
 
     // ---- query fragments (B operand: lane l = query row l%16, dims 8*(l/16)..+7 of each 32-dim step)
     bf16x8 qf[RBW][KFR];
@@ -94,8 +99,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
 
     // ---- tile loader: 16-byte unit u of the tile belongs to segment u / UNITS_PER_SEG
     auto issue = [&](int ti, int stage) {
-        const int pg0 = __builtin_amdgcn_readlane(my_page, 2 * ti);
-        const int pg1 = __builtin_amdgcn_readlane(my_page, 2 * ti + 1);     // clamped to the last page at load
+        int pg0 = 0, pg1 = 0;                                          // page 2*ti and 2*ti+1 of the chunk
+#pragma unroll
+        for (int q = 0; q < NPREG; ++q)
+            if ((ti >> 5) == q) {                                     // uniform: 32 tiles per register of ids
+                pg0 = __builtin_amdgcn_readlane(my_page[q], (2 * ti) & 63);
+                pg1 = __builtin_amdgcn_readlane(my_page[q], (2 * ti + 1) & 63);   // clamped to the last page at load
+            }
 #pragma unroll
         for (int jn = 0; jn < NLOAD; ++jn) {
             const int u = tid + jn * 256;
@@ -150,10 +160,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(PassMeta pm, const in
                 mt = fmaxf(mt, __shfl_xor(mt, 32));    // the row's maximum, same in its four lanes
                 const float mn = (mt > m_run[i] + 8.f) ? mt : m_run[i];
                 const float alpha = exp2f(m_run[i] - ((mn == -INFINITY) ? 0.f : mn));   // 1 for rows that stay
+                const bool had_sum = m_run[i] != -INFINITY && alpha != 1.f;            // a first tile has nothing to rescale
                 l_run[i] *= alpha;
                 m_run[i] = mn;
+                if (__any(had_sum)) {                  // rare: a reference moving after the row's first tile
 #pragma unroll
-                for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
+                    for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
+                }
             }
             const float ms = (m_run[i] == -INFINITY) ? 0.f : m_run[i];
             float ps = 0.f;
@@ -221,7 +234,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     dim3 g(n_items, dm.Hkv), blk(256);
     const size_t lds = 0;     // tile stages are static LDS arrays
 #define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB><<<g, blk, lds, st>>>(pm, items, qkv, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.qkvN, sc)
+    attn_partial_kernel<DD, RB, 4, (RB <= 2 ? 2 : 1)><<<g, blk, lds, st>>>(pm, items, qkv, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.qkvN, sc)
     if (dm.D == 128) {
         if (rbw == 1) ATTN_LAUNCH(128, 1); else if (rbw == 2) ATTN_LAUNCH(128, 2); else ATTN_LAUNCH(128, 4);
     } else {

@@ -176,7 +176,7 @@ void launch_rope_kv(const PassMeta &pm, bf16_t *qkv, const float *cs, bf16_t *kp
 // ---------------------------------------------------------------- KV import / export / synthetic fill
 // linear layout [n_pos][Hkv][D]; grid (n_pos, Hkv), block D
 __global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int first_pos, bf16_t *kpool, bf16_t *vpool,
-                             bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D) {
+                             bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages) {
     int p = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
     int pos = first_pos + p;
     size_t blk = ((size_t)page_row[pos >> 4] * Hkv + hd) * (size_t)(DAS_PAGE * D);
@@ -191,9 +191,9 @@ __global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int fir
     }
 }
 void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_t *kpool_layer, bf16_t *vpool_layer,
-                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, hipStream_t st) {
+                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, hipStream_t st) {
     if (n_pos > 0)
-        kv_io_kernel<<<dim3(n_pos, Hkv), dim3(D), 0, st>>>(mode, page_row, first_pos, kpool_layer, vpool_layer, k_lin, v_lin, Hkv, D);
+        kv_io_kernel<<<dim3(n_pos, Hkv), dim3(D), 0, st>>>(mode, page_row, first_pos, kpool_layer, vpool_layer, k_lin, v_lin, Hkv, D, num_pages);
 }
 
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {
@@ -207,7 +207,7 @@ __device__ __forceinline__ bf16_t synth_value(uint64_t base, uint64_t e) {
     int s = (int)(h & 0xFFFF) + (int)((h >> 16) & 0xFFFF) + (int)((h >> 32) & 0xFFFF) + (int)(h >> 48) - 131070;
     return f2bf((float)s * (1.0f / 32768.0f));
 }
-__global__ void kv_synth_kernel(const int *__restrict__ page_row, bf16_t *kpool, bf16_t *vpool, int Hkv, int D,
+__global__ void kv_synth_kernel(const int *__restrict__ page_row, bf16_t *kpool, bf16_t *vpool, int Hkv, int D, int num_pages,
                                 uint64_t base_k, uint64_t base_v) {
     int pos = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
     size_t blk = ((size_t)page_row[pos >> 4] * Hkv + hd) * (size_t)(DAS_PAGE * D);
@@ -222,12 +222,12 @@ static uint64_t host_mix64(uint64_t z) {
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
-void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D,
+void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D, int num_pages,
                      uint64_t seed, uint64_t seq_key, int layer, hipStream_t st) {
     if (ctx <= 0) return;
     uint64_t b = host_mix64(host_mix64(seed ^ 0x4B5653594E544821ull) ^ seq_key);
     uint64_t bk = host_mix64(b ^ ((uint64_t)layer * 2u)), bv = host_mix64(b ^ ((uint64_t)layer * 2u + 1u));
-    kv_synth_kernel<<<dim3(ctx, Hkv), dim3(D), 0, st>>>(page_row, kpool_layer, vpool_layer, Hkv, D, bk, bv);
+    kv_synth_kernel<<<dim3(ctx, Hkv), dim3(D), 0, st>>>(page_row, kpool_layer, vpool_layer, Hkv, D, num_pages, bk, bv);
 }
 
 // ---------------------------------------------------------------- plain copy (counter calibration)
