@@ -99,13 +99,10 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
 
     // ---- tile loader: 16-byte unit u of the tile belongs to segment u / UNITS_PER_SEG
     auto issue = [&](int ti, int stage) {
-        int pg0 = 0, pg1 = 0;                                          // page 2*ti and 2*ti+1 of the chunk
-#pragma unroll
-        for (int q = 0; q < NPREG; ++q)
-            if ((ti >> 5) == q) {                                     // uniform: 32 tiles per register of ids
-                pg0 = __builtin_amdgcn_readlane(my_page[q], (2 * ti) & 63);
-                pg1 = __builtin_amdgcn_readlane(my_page[q], (2 * ti + 1) & 63);   // clamped to the last page at load
-            }
+        // pages 2*ti and 2*ti+1 of the chunk (the second one was clamped to the last page at load)
+        static_assert(NPREG == 1, "one register of 64 page ids covers a chunk");
+        const int pg0 = __builtin_amdgcn_readlane(my_page[0], 2 * ti);
+        const int pg1 = __builtin_amdgcn_readlane(my_page[0], 2 * ti + 1);
 #pragma unroll
         for (int jn = 0; jn < NLOAD; ++jn) {
             const int u = tid + jn * 256;
