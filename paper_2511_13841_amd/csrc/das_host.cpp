@@ -55,7 +55,8 @@ struct das_model {
     int *page_table = nullptr;
     // workspaces
     float *h = nullptr, *cs = nullptr, *logits = nullptr, *row_stats = nullptr;
-    bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
+    bf16_t *xn = nullptr, *q_hi = nullptr, *q_lo = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
+    float *qkv = nullptr;                  // fp32 projections of the pass: rounded to bf16 once, after RoPE
     float *part_acc = nullptr, *part_ml = nullptr;
     size_t part_rows_cap = 0;
     int *d_g = nullptr, *d_accept = nullptr, *d_next = nullptr;
@@ -231,12 +232,12 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         const LayerW &w = m->layers[l];
         bf16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
-        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_BF16_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st); }
-        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->cs, kl, vl, dm, st); }
+        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st); }
+        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->q_hi, m->q_lo, m->cs, kl, vl, dm, st); }
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)
-                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->qkv, kl, vl, m->part_acc, m->part_ml, dm, st);
+                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_hi, m->q_lo, kl, vl, m->part_acc, m->part_ml, dm, st);
         }
         { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_acc, m->part_ml, m->attn, dm, st); }
         { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st); }
@@ -353,7 +354,7 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     A(m->page_table, (size_t)c.max_seqs * m->max_pages);
     HIPCHK(hipMemsetAsync(m->page_table, 0, (size_t)c.max_seqs * m->max_pages * sizeof(int), m->st));
     // ---- workspaces (row counts padded to 256 so GEMM tiles may over-read)
-    A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
+    A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->q_hi, Mp * qd); A(m->q_lo, Mp * qd); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
     A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
     A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs);
     HIPCHK(hipMemsetAsync(m->xn, 0, Mp * d * 2, m->st));

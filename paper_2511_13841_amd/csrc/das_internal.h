@@ -82,12 +82,14 @@ void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStrea
 // y (fragment order, K = d) = rmsnorm(h[row]) for row = sel ? sel[i] : i, i < n
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st);
 void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, int D, hipStream_t st);
-void launch_rope_kv(const PassMeta &pm, bf16_t *qkv, const float *cs, bf16_t *kpool_layer, bf16_t *vpool_layer,
-                    const DasDims &dm, hipStream_t st);
+// qkv: fp32 [T][qkvN] projections; q is rotated and split into two bf16 terms q_hi + q_lo ([T][Hq*D] each);
+// k is rotated, rounded once and scattered into its page; v is rounded once and scattered
+void launch_rope_kv(const PassMeta &pm, const float *qkv, bf16_t *q_hi, bf16_t *q_lo, const float *cs,
+                    bf16_t *kpool_layer, bf16_t *vpool_layer, const DasDims &dm, hipStream_t st);
 // C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
 void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st);
 // split-KV partial attention for the items of one row-block class, then the merge
-void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *qkv,
+void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
                  const bf16_t *kpool_layer, const bf16_t *vpool_layer, float *part_acc, float *part_ml,
                  const DasDims &dm, hipStream_t st);
 void launch_attn_merge(const PassMeta &pm, const float *part_acc, const float *part_ml, bf16_t *out_frag,

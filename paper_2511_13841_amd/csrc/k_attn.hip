@@ -33,11 +33,12 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // without copies out of the accumulation register file on every tile.
 template <int D, int RBW, int NS, int MINW>
 __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
-                                                           const bf16_t *__restrict__ qkv,
+                                                           const bf16_t *__restrict__ q_hi,
+                                                           const bf16_t *__restrict__ q_lo,
                                                            const bf16_t *__restrict__ kpool,
                                                            const bf16_t *__restrict__ vpool,
                                                            float *__restrict__ part_acc, float *__restrict__ part_ml,
-                                                           int Hkv, int G, int qkvN, float scale_log2e) {
+                                                           int Hkv, int G, int qstride, float scale_log2e) {
     constexpr int KFR = D / 32;            // K fragments (1 KiB) per page
     constexpr int VDB = D / 16;            // V dim blocks (512 B) per page
     constexpr int PAGE_E = DAS_PAGE * D;   // elements of one (page, head) block
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
     for (int q = 0; q < NPREG; ++q) my_page[q] = pt[min(first_page + q * 64 + lane, npages - 1)];
 
     // ---- query fragments (B operand: lane l = query row l%16, dims 8*(l/16)..+7 of each 32-dim step)
-    bf16x8 qf[RBW][KFR];
+    bf16x8 qf[RBW][KFR], ql[RBW][KFR];     // q = qf + ql: two bf16 terms, so the scores see q at ~16 bits
     int lim[RBW];           // last KV position this lane's query row may see (-1: padding row)
     bool any_active = false;
 #pragma unroll
@@ -80,11 +81,13 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
         const int j = valid ? rr / G : 0, g = valid ? rr % G : 0;
         lim[i] = valid ? ctx + j : -1;
         any_active |= ((wave * RBW + i) * 16 < R);
-        const bf16_t *src = qkv + (size_t)(row0 + j) * qkvN + (size_t)(kvh * G + g) * D + 8 * (lane >> 4);
+        const size_t qo = (size_t)(row0 + j) * qstride + (size_t)(kvh * G + g) * D + 8 * (lane >> 4);
 #pragma unroll
         for (int ks = 0; ks < KFR; ++ks) {
-            uint4 v = valid ? *reinterpret_cast<const uint4 *>(src + ks * 32) : make_uint4(0, 0, 0, 0);
+            uint4 v = valid ? *reinterpret_cast<const uint4 *>(q_hi + qo + ks * 32) : make_uint4(0, 0, 0, 0);
+            uint4 w = valid ? *reinterpret_cast<const uint4 *>(q_lo + qo + ks * 32) : make_uint4(0, 0, 0, 0);
             qf[i][ks] = *reinterpret_cast<bf16x8 *>(&v);
+            ql[i][ks] = *reinterpret_cast<bf16x8 *>(&w);
         }
     }
 
@@ -127,10 +130,12 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
             for (int i = 0; i < RBW; ++i) {
                 s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s[i][0], 0, 0, 0);
                 s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s[i][1], 0, 0, 0);
+                s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[i][ks], s[i][0], 0, 0, 0);
+                s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[i][ks], s[i][1], 0, 0, 0);
             }
         }
         const bool need_mask = tile_tok0 + DAS_ATTN_TILE - 1 > ctx;
-        bf16x8 pf[RBW];
+        bf16x8 pf[RBW], pl[RBW];               // probabilities as two bf16 terms as well
 #pragma unroll
         for (int i = 0; i < RBW; ++i) {
             // Softmax with a lazily updated reference: p = exp2(s - m_ref).  m_ref only moves when the row's
@@ -172,7 +177,10 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
             for (int r = 0; r < 8; ++r) { pv[r] = __builtin_amdgcn_exp2f(sv[r] - ms); ps += pv[r]; }
             l_run[i] += ps;
 #pragma unroll
-            for (int r = 0; r < 8; ++r) pf[i][r] = (__bf16)pv[r];
+            for (int r = 0; r < 8; ++r) {
+                pf[i][r] = (__bf16)pv[r];
+                pl[i][r] = (__bf16)(pv[r] - (float)pf[i][r]);
+            }
         }
         // O^T += V^T P^T : A = V fragment (dims x 32 token slots), B = probabilities
 #pragma unroll
@@ -183,7 +191,10 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
             const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
 #pragma unroll
             for (int i = 0; i < RBW; ++i)
+            {
                 acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[i], acc[i][db], 0, 0, 0);
+                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl[i], acc[i][db], 0, 0, 0);
+            }
         }
     };
 
@@ -223,7 +234,7 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
     }
 }
 
-void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *qkv,
+void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
                  const bf16_t *kpool_layer, const bf16_t *vpool_layer, float *part_acc, float *part_ml,
                  const DasDims &dm, hipStream_t st) {
     if (n_items <= 0) return;
@@ -231,7 +242,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     dim3 g(n_items, dm.Hkv), blk(256);
     const size_t lds = 0;     // tile stages are static LDS arrays
 #define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB, 4, (RB <= 2 ? 2 : 1)><<<g, blk, lds, st>>>(pm, items, qkv, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.qkvN, sc)
+    attn_partial_kernel<DD, RB, 4, (RB <= 2 ? 2 : 1)><<<g, blk, lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     if (dm.D == 128) {
         if (rbw == 1) ATTN_LAUNCH(128, 1); else if (rbw == 2) ATTN_LAUNCH(128, 2); else ATTN_LAUNCH(128, 4);
     } else {

@@ -141,19 +141,28 @@ void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, in
     rope_table_kernel<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(pm.row_pos, inv_freq, reinterpret_cast<float2 *>(cs), pm.T, D / 2);
 }
 
-// ---------------------------------------------------------------- RoPE on q (in place) and k; K/V rows -> pages
-// grid (T, Hq + 2 Hkv), block D/2: thread i owns the rotate-half pair (i, i + D/2).
-__global__ void rope_kv_kernel(PassMeta pm, bf16_t *__restrict__ qkv, const float2 *__restrict__ cs,
-                               bf16_t *__restrict__ kpool, bf16_t *__restrict__ vpool, int Hq, int Hkv, int D, int qkvN) {
+// ---------------------------------------------------------------- RoPE on q and k; q split hi/lo; K/V rows -> pages
+// grid (T, Hq + 2 Hkv), block D/2: thread i owns the rotate-half pair (i, i + D/2).  The projections arrive in
+// fp32 and are rounded to bf16 exactly once, after the rotation.  q keeps a second bf16 term (q - bf16(q)) so
+// that the scores see it at ~16 bits: the attention kernel multiplies K by both terms.
+__global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, bf16_t *__restrict__ q_hi, bf16_t *__restrict__ q_lo,
+                               const float2 *__restrict__ cs, bf16_t *__restrict__ kpool, bf16_t *__restrict__ vpool,
+                               int Hq, int Hkv, int D, int qkvN) {
     int r = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = D >> 1;
-    bf16_t *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
-    float x1 = bf2f(row[i]), x2 = bf2f(row[i + half]);
+    const float *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
+    float x1 = row[i], x2 = row[i + half];
     if (hh < Hq + Hkv) {
         float2 c = cs[r * half + i];
         float y1 = x1 * c.x - x2 * c.y, y2 = x2 * c.x + x1 * c.y;
         x1 = y1; x2 = y2;
     }
-    if (hh < Hq) { row[i] = f2bf(x1); row[i + half] = f2bf(x2); return; }
+    if (hh < Hq) {
+        const size_t o = (size_t)r * Hq * D + (size_t)hh * D;
+        const bf16_t h1 = f2bf(x1), h2 = f2bf(x2);
+        q_hi[o + i] = h1; q_hi[o + i + half] = h2;
+        q_lo[o + i] = f2bf(x1 - bf2f(h1)); q_lo[o + i + half] = f2bf(x2 - bf2f(h2));
+        return;
+    }
     int b = pm.row_b[r], pos = pm.row_pos[r];
     int page = pm.page_table[(size_t)pm.b_slot[b] * pm.max_pages + (pos >> 4)];
     int t = pos & 15;
@@ -163,14 +172,14 @@ __global__ void rope_kv_kernel(PassMeta pm, bf16_t *__restrict__ qkv, const floa
         blk[kpage_off(t, i + half)] = f2bf(x2);
     } else {
         bf16_t *blk = vpool + ((size_t)page * Hkv + (hh - Hq - Hkv)) * (size_t)(DAS_PAGE * D);
-        blk[vpage_off(t, i)] = row[i];
-        blk[vpage_off(t, i + half)] = row[i + half];
+        blk[vpage_off(t, i)] = f2bf(x1);
+        blk[vpage_off(t, i + half)] = f2bf(x2);
     }
 }
-void launch_rope_kv(const PassMeta &pm, bf16_t *qkv, const float *cs, bf16_t *kpool_layer, bf16_t *vpool_layer,
-                    const DasDims &dm, hipStream_t st) {
+void launch_rope_kv(const PassMeta &pm, const float *qkv, bf16_t *q_hi, bf16_t *q_lo, const float *cs,
+                    bf16_t *kpool_layer, bf16_t *vpool_layer, const DasDims &dm, hipStream_t st) {
     rope_kv_kernel<<<dim3(pm.T, dm.Hq + 2 * dm.Hkv), dim3(dm.D / 2), 0, st>>>(
-        pm, qkv, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
+        pm, qkv, q_hi, q_lo, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
 }
 
 // ---------------------------------------------------------------- KV import / export / synthetic fill

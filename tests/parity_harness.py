@@ -72,3 +72,35 @@ def check_bookkeeping(dm, mirror, seq_ids, pendings):
         assert st["pending"] == int(pend)
         assert st["pages"] == mirror.pages[sid], (sid, st["pages"], mirror.pages[sid])
     assert dm.debug_free_pages() == len(mirror.free)
+
+
+def check_sampled_token(w, u, v, eps):
+    """The GPU's token v must satisfy u*Z in [prefix(v-1) - eps*Z, prefix(v) + eps*Z] under the oracle's weights."""
+    cs = np.cumsum(w)
+    Z = cs[-1]
+    lo = cs[v - 1] if v > 0 else 0.0
+    assert w[v] > 0.0, "sampled a zero-weight token"
+    assert lo - eps * Z <= u * Z <= cs[v] + eps * Z, (v, u * Z, lo, cs[v], eps * Z)
+
+
+def compare_stochastic_step(gpu_logits, gpu_accept, gpu_next, oracle_logits, drafts, tau, u_accept, u_sample):
+    """One sequence of one stochastic step.  Returns True when the decision was compared exactly, False when it
+    was flagged (a uniform within e^{+-0.1} of an accept probability on the way to the oracle's decision)."""
+    from oracle import softmax_weights, stochastic_accept
+    err = float(np.abs(gpu_logits.astype(np.float64) - oracle_logits.astype(np.float64)).max())
+    assert err <= LOGIT_RTOL * float(np.abs(oracle_logits).max())
+    a, _ = stochastic_accept(oracle_logits, drafts, tau, u_accept, u_sample)
+    k = len(drafts)
+    for j in range(min(a + 1, k)):
+        w, Z = softmax_weights(oracle_logits[j], tau)
+        pd = w[int(drafts[j])] / Z
+        if pd * np.exp(-0.1) <= float(u_accept[j]) <= pd * np.exp(0.1):
+            return False
+    assert int(gpu_accept) == a, (int(gpu_accept), a)
+    w, _ = softmax_weights(oracle_logits[a], tau)
+    if a < k:
+        w = w.copy()
+        w[int(drafts[a])] = 0.0
+        assert int(gpu_next) != int(drafts[a])
+    check_sampled_token(w, float(u_sample[a]), int(gpu_next), np.exp(2 * err / tau) - 1 + 1e-6)
+    return True
