@@ -74,6 +74,7 @@ class Rollout:
         self.ctx = self.ctx0.copy()
         self.pending = self.pending0.copy()
         self.future = None
+        self.faithful = False
 
     def generate_trajectories(self):
         """Plain decoding (k=0 verify steps) for `horizon` tokens, then rewind.  future[i][0] is the pending token."""
@@ -101,9 +102,24 @@ class Rollout:
         self.proposal = rng.integers(0, self.shape.vocab, size=(self.B, self.horizon + 1), dtype=np.int32)
         self.emitted = np.ones(self.B, np.int64)
 
+    def sampling_inputs(self, ks):
+        """Seeded uniforms of a stochastic step, one pair per row, keyed by (sequence, absolute position).
+        Controlled mode: a draft position is force-accepted (u_accept = 0) with the drafter's probability p,
+        otherwise judged honestly (p_target of a random token under random-init weights is ~1e-5)."""
+        keys = np.repeat(np.arange(self.B), ks + 1)
+        pos = np.concatenate([np.arange(c, c + k + 1) for c, k in zip(self.ctx, ks)])
+        ua = di.uniforms(self.seed, keys, pos, 0)
+        us = di.uniforms(self.seed, keys, pos, 1)
+        if not self.faithful:
+            force = di.uniforms(self.seed, keys, pos, 2) < self.wl.accept_p
+            ua = np.where(force, 0.0, ua).astype(np.float32)
+        return (self.wl.temperature, ua, us)
+
     def step(self, sampling=None):
         ks = di.draft_budgets(self.wl, self.ctx)
         drafts = [self.proposal[i, self.emitted[i]:self.emitted[i] + ks[i]] for i in range(self.B)]
+        if sampling is None and self.wl.mode == "stochastic":
+            sampling = self.sampling_inputs(ks)
         acc, nxt = self.dm.verify_step(self.ids, self.ctx, drafts, sampling)
         self.dm.kv_commit(self.ids, acc, nxt)
         self.ctx = self.ctx + 1 + acc
@@ -207,7 +223,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--context", default="synth", choices=["synth", "prefill"])
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
@@ -215,6 +231,8 @@ def main():
                     help="random: uniform random drafts, no plain-decoding pass (same kernel shapes; for profiler runs)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also launch a plain copy kernel of this size 3 times (profiler byte-counter reference)")
+    ap.add_argument("--faithful", action="store_true",
+                    help="stochastic workload: honest accept uniforms everywhere (acceptance ~0 on random-init weights)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     args = ap.parse_args()
@@ -227,7 +245,8 @@ def main():
     wl = di.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
     ro = Rollout(wl, batch=args.batch, n_layers=args.layers, context=args.context, max_steps=W + 2 * K + 1)
-    if args.drafts == "trajectory":
+    ro.faithful = args.faithful
+    if args.drafts == "trajectory" and wl.mode == "greedy":
         ro.generate_trajectories()
     else:
         ro.random_proposals()
@@ -270,7 +289,7 @@ def main():
         ro.das.debug_copy(args.calibrate_copy << 20, 3)
 
     cpu = None
-    if not args.no_cpu_baseline and args.drafts == "trajectory":
+    if not args.no_cpu_baseline and args.drafts == "trajectory" and wl.mode == "greedy":
         cpu = cpu_baseline(ro)
 
     out = {
