@@ -167,13 +167,13 @@ def stored_traffic(workload, kernel_class):
     """HBM-side bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
     scaled by the plain copy kernel), if one exists for this workload and kernel class; else None."""
     path = os.path.join(ROOT, "profiles", f"verify_step_{workload}_traffic.json")
-    prefix = {"attention": "void attn_partial_kernel", "gemm_gateup_silu": "void gemm_kernel<2, 2, 2, 2, 2>",
-              "gemm_qkv": "void gemm_kernel<2, 2, 2, 2, 0>", "gemm_lm_head": "void gemm_kernel<2, 2, 2, 2, 3>",
-              "attention_merge": "void attn_merge_kernel"}.get(kernel_class)
-    if not prefix or not os.path.exists(path):
+    match = {"attention": lambda k: k.startswith("attn_partial_kernel"),
+             "attention_merge": lambda k: k.startswith("attn_merge_kernel"),
+             "gemm_gateup_silu": lambda k: k.startswith("gemm_kernel") and k.endswith(", 2>")}.get(kernel_class)
+    if not match or not os.path.exists(path):
         return None
     per = json.load(open(path))["per_launch"]
-    hits = [v for k, v in per.items() if k.startswith(prefix)]
+    hits = [v for k, v in per.items() if match(k)]
     return sum(v["fetch_bytes"] + v["write_bytes"] for v in hits) if hits else None
 
 

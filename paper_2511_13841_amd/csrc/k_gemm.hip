@@ -229,7 +229,13 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         else launch_one<4, 1, 2, 2, 3, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
         return;
     }
-    if (M > 256 && N >= 16384) launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
+    if (M > 256 && N >= 16384) {
+        // 256-row or 288-row tiles (12 waves, 3 x 4), whichever pads M less: T = 1088 is 4 x 288 - 64 but 5 x 256 - 192
+        const int pad256 = (M + 255) / 256 * 256, pad288 = (M + 287) / 288 * 288;
+        if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
+        else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
+        return;
+    }
     else if (epi == EPI_SILU_FRAG) {
         if (M > 512) launch_one<4, 2, 1, 2, 4, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
         else launch_one<4, 1, 1, 2, 5, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
