@@ -191,7 +191,9 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         const int nchunk = (pb.start + pb.n + DAS_ATTN_CHUNK - 1) / DAS_ATTN_CHUNK;
         b_prow[b] = (int)prow; b_nchunk[b] = nchunk;
         prow += (size_t)nchunk * R;
-        const int cls = nrb <= 4 ? 0 : (nrb <= 8 ? 1 : 2);
+        // two kernel shapes: up to 8 row blocks of 16 query rows per KV head (2 per wave), or up to 16 (4 per wave).
+        // One launch for everything up to 8 blocks lets short sequences fill the tail of the long ones.
+        const int cls = nrb <= 8 ? 1 : 2;
         for (int c = 0; c < nchunk; ++c) { items[cls].push_back(b); items[cls].push_back(c); }
         for (int j = 0; j < pb.n; ++j, ++r) {
             tok[r] = pb.toks[j]; row_pos[r] = pb.start + j; row_b[r] = b;
@@ -199,6 +201,17 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         }
     }
     if (prow > 0x7FFFFFFFull) return DAS_ERR_NOMEM;
+    // longest work items first, so that the short last chunks fill the tail of the launch
+    for (int c = 0; c < 3; ++c) {
+        std::vector<std::pair<int, int>> v;
+        for (size_t i = 0; i + 1 < items[c].size(); i += 2) v.push_back({items[c][i], items[c][i + 1]});
+        auto tokens = [&](const std::pair<int, int> &it) {
+            const int total = blocks[it.first].start + blocks[it.first].n;
+            return std::min(total - it.second * DAS_ATTN_CHUNK, DAS_ATTN_CHUNK);
+        };
+        std::stable_sort(v.begin(), v.end(), [&](const std::pair<int, int> &a, const std::pair<int, int> &b) { return tokens(a) > tokens(b); });
+        for (size_t i = 0; i < v.size(); ++i) { items[c][2 * i] = v[i].first; items[c][2 * i + 1] = v[i].second; }
+    }
     int *item_ptr[3];
     for (int c = 0; c < 3; ++c) { item_ptr[c] = p; std::copy(items[c].begin(), items[c].end(), p); p += items[c].size(); }
     const int n_upd = (int)m->pending_upd.size() / 2;
