@@ -26,22 +26,23 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
 
-// WGM x WGN waves, each owning TM x TN blocks of 32x32.  BK = 64 (4 MFMA k-steps).  NS LDS stages form a
+// WGM x WGN waves, each owning TM x TN blocks of 32x32.  A k-tile is KS MFMA k-steps (BK = 16*KS: 64 or 32).  NS LDS stages form a
 // ring: while k-tile kt is multiplied, k-tiles kt+1 .. kt+NS-2 are already in flight and the stage of
 // kt-1 is being refilled with kt+NS-1.
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3)>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
                                                              int tiles_m, int tiles_n) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int AB = WGM * TM, BB = WGN * TN;          // 32-row blocks per tile
-    constexpr int A_UNITS = AB * 256, B_UNITS = BB * 256; // 16-byte units per k-tile
+    constexpr int RBU = KS * 64;                          // 16-byte units of one row block in one k-tile
+    constexpr int A_UNITS = AB * RBU, B_UNITS = BB * RBU; // 16-byte units per k-tile
     constexpr int UNITS = A_UNITS + B_UNITS;
     constexpr int NLOAD = (UNITS + NT - 1) / NT;         // every wave issues NLOAD copies per k-tile, so that one
     constexpr bool PADDED = (UNITS % NT) != 0;           // s_waitcnt fits all; surplus copies go to a dump area
     static_assert((NS - 2) * NLOAD <= 63, "vmcnt is a 6-bit counter");
     static_assert(EPI != EPI_SILU_FRAG || TN % 2 == 0, "gate and up blocks must sit in the same wave");
-    constexpr int STAGE_BYTES = (AB + BB) * 4096;
+    constexpr int STAGE_BYTES = (AB + BB) * KS * 1024;
     extern __shared__ __align__(16) unsigned char smem[];
 
     // XCD-aware tile order: the workgroups of one XCD (id % 8) walk a contiguous
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int KF = K >> 4;                                 // fragments per row block
-    const int KT = K >> 6;                                 // k-tiles
+    const int KT = K / (16 * KS);                          // k-tiles
     const uint4 *Ag = reinterpret_cast<const uint4 *>(A);
     const uint4 *Wg = reinterpret_cast<const uint4 *>(W);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem + wave * 1024;
@@ -65,8 +66,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
     for (int j = 0; j < NLOAD; ++j) {
         const int u = min(tid + j * NT, UNITS - 64 + lane);      // surplus waves re-read the last fragment
-        if (u < A_UNITS) src[j] = Ag + ((size_t)(tile_m * AB + (u >> 8)) * KF) * 64 + (u & 255);
-        else { const int v = u - A_UNITS; src[j] = Wg + ((size_t)(tile_n * BB + (v >> 8)) * KF) * 64 + (v & 255); }
+        if (u < A_UNITS) src[j] = Ag + ((size_t)(tile_m * AB + u / RBU) * KF) * 64 + (u % RBU);
+        else { const int v = u - A_UNITS; src[j] = Wg + ((size_t)(tile_n * BB + v / RBU) * KF) * 64 + (v % RBU); }
     }
     // surplus copies of the last pass (whole waves: UNITS is a multiple of 64) land behind the ring
     const bool surplus = PADDED && (wave * 64 + (NLOAD - 1) * NT >= UNITS);
@@ -79,27 +80,38 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    auto issue = [&](int kt, int stage) {                  // 4 fragments = 256 uint4 per k-tile and row block
+    auto issue = [&](int kt, int stage) {                  // KS fragments = RBU uint4 per k-tile and row block
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j)
-            dma16(src[j] + (size_t)kt * 256, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
+            dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
                                                                          : lds_base + stage * STAGE_BYTES + j * NT * 16);
     };
-    auto compute = [&](const unsigned char *cur) {
+    // the copies of one k-tile, cut into KS slices that are issued between the MFMA k-steps: sixteen copies
+    // issued back to back would fill the vector-memory queue and stall the wave that should be multiplying
+    auto issue_slice = [&](int kt, int stage, int slice) {
+#pragma unroll
+        for (int j = 0; j < NLOAD; ++j)
+            if (j % KS == slice)
+                dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
+                                                                             : lds_base + stage * STAGE_BYTES + j * NT * 16);
+    };
+    auto compute = [&](const unsigned char *cur, int next_kt, int next_stage) {
         // fragments of k-step ks+1 are requested before the MFMAs of k-step ks are issued
         bf16x8 a[2][TM], b[2][TN];
         auto fetch = [&](int ks, int buf) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                a[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + i) * 4 + ks) * 1024 + lane * 16);
+                a[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + i) * KS + ks) * 1024 + lane * 16);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                b[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + AB * 4096 + ((wn * TN + j) * 4 + ks) * 1024 + lane * 16);
+                b[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((wn * TN + j) * KS + ks) * 1024 + lane * 16);
         };
         fetch(0, 0);
+        if (!SPREAD) issue(next_kt, next_stage);     // two stages and many rows: no slack, request the next tile at once
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) fetch(ks + 1, (ks + 1) & 1);
+        for (int ks = 0; ks < KS; ++ks) {
+            if (SPREAD) issue_slice(next_kt, next_stage, ks);
+            if (ks < KS - 1) fetch(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -123,8 +135,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
         __builtin_amdgcn_s_barrier();      // tile kt visible to all waves; all waves are done with tile kt-1
         asm volatile("" ::: "memory");
         const int refill = stage == 0 ? NS - 1 : stage - 1;
-        issue(min(kt + NS - 1, last), refill);
-        compute(smem + stage * STAGE_BYTES);
+        compute(smem + stage * STAGE_BYTES, min(kt + NS - 1, last), refill);
         stage = stage == NS - 1 ? 0 : stage + 1;
     }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
@@ -175,13 +186,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     }
 }
 
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3)>
 static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    constexpr int LDS = NS * (WGM * TM + WGN * TN) * 4096 + WGM * WGN * 1024;      // ring + dump area for padded copies
+    constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
     static bool configured = false;
-    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI>;
+    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD>;
     if (!configured) {      // dynamic LDS above the default limit has to be granted once per kernel
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
@@ -233,6 +244,8 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // 256-row or 288-row tiles (12 waves, 3 x 4), whichever pads M less: T = 1088 is 4 x 288 - 64 but 5 x 256 - 192
         const int pad256 = (M + 255) / 256 * 256, pad288 = (M + 287) / 288 * 288;
         if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
+        else if (M <= 512 && epi == EPI_F32_ROWMAJOR)      // few rows (LM head at T ~ 300): spread the copies over the k-steps
+            launch_one<2, 4, 4, 2, 2, EPI_F32_ROWMAJOR, 4, true>(A, W, C, M, N, K, ldc, st);
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
         return;
     }
