@@ -14,7 +14,7 @@
 //     reduced from scratch, then chunks are merged in ascending order: a row's
 //     result does not depend on the batch it is verified in (speculative
 //     verification and one-token decoding give bit-identical rows).
-// Wave w owns query-row blocks (16 rows each) w*RBW .. w*RBW+RBW-1.
+// Wave w (of 8) owns query-row blocks (16 rows each) w*RBW .. w*RBW+RBW-1.
 #include "das_internal.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -31,8 +31,8 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // Two waves per SIMD are asked for whenever the row blocks fit 256 registers: besides the occupancy, it
 // makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
 // without copies out of the accumulation register file on every tile.
-template <int D, int RBW, int NS, int MINW>
-__global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
+template <int D, int RBW, int NS, int MINW, int NW>
+__global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const bf16_t *__restrict__ q_hi,
                                                            const bf16_t *__restrict__ q_lo,
                                                            const bf16_t *__restrict__ kpool,
@@ -45,7 +45,9 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
     constexpr int PAGE_B = PAGE_E * 2;
     constexpr int TILE_B = 4 * PAGE_B;     // K page0, K page1, V page0, V page1
     constexpr int UNITS_PER_SEG = PAGE_B / 16;
-    constexpr int NLOAD = (TILE_B / 16) / 256;
+    constexpr int NT = NW * 64;
+    constexpr int NLOAD = (TILE_B / 16) / NT;
+    static_assert((TILE_B / 16) % NT == 0, "tile must divide over the threads");
     // ring of NS tile stages: one being read, NS-1 being filled
     __shared__ __align__(16) unsigned char smem[NS * TILE_B];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
@@ -108,11 +110,11 @@ __global__ __launch_bounds__(256, MINW) void attn_partial_kernel(PassMeta pm, co
         const int pg1 = __builtin_amdgcn_readlane(my_page[0], 2 * ti + 1);
 #pragma unroll
         for (int jn = 0; jn < NLOAD; ++jn) {
-            const int u = tid + jn * 256;
+            const int u = tid + jn * NT;
             const int seg = u / UNITS_PER_SEG, off = u % UNITS_PER_SEG;
             const int pg = (seg & 1) ? pg1 : pg0;
             const bf16_t *base = (seg < 2 ? kpool : vpool) + ((size_t)pg * Hkv + kvh) * PAGE_E;
-            dma16(reinterpret_cast<const uint4 *>(base) + off, lds_base + stage * TILE_B + jn * 4096 + wave * 1024);
+            dma16(reinterpret_cast<const uint4 *>(base) + off, lds_base + stage * TILE_B + jn * NT * 16 + wave * 1024);
         }
     };
 
@@ -241,12 +243,15 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
     dim3 g(n_items, dm.Hkv), blk(256);
     const size_t lds = 0;     // tile stages are static LDS arrays
+    // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
+    // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
 #define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB, 4, (RB <= 2 ? 2 : 1)><<<g, blk, lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
     if (dm.D == 128) {
-        if (rbw == 1) ATTN_LAUNCH(128, 1); else if (rbw == 2) ATTN_LAUNCH(128, 2); else ATTN_LAUNCH(128, 4);
+        if (rbw <= 2) ATTN_LAUNCH(128, 1); else ATTN_LAUNCH(128, 2);
     } else {
-        if (rbw == 1) ATTN_LAUNCH(64, 1); else if (rbw == 2) ATTN_LAUNCH(64, 2); else ATTN_LAUNCH(64, 4);
+        if (rbw <= 2) ATTN_LAUNCH(64, 1); else ATTN_LAUNCH(64, 2);
     }
 #undef ATTN_LAUNCH
 }
