@@ -57,7 +57,8 @@ struct das_model {
     float *h = nullptr, *cs = nullptr, *logits = nullptr, *row_stats = nullptr;
     bf16_t *xn = nullptr, *q_hi = nullptr, *q_lo = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
     float *qkv = nullptr;                  // fp32 projections of the pass: rounded to bf16 once, after RoPE
-    float *part_acc = nullptr, *part_ml = nullptr;
+    uint16_t *part_o = nullptr;      // split-KV partial outputs (fp16, normalised per chunk)
+    float *part_ml = nullptr;        // their (m, l) per row
     size_t part_rows_cap = 0;
     int *d_g = nullptr, *d_accept = nullptr, *d_next = nullptr;
     // staging
@@ -142,18 +143,19 @@ static void shrink_pages(das_model *m, int slot, int tokens) {
     while ((int)s.pages.size() > pages_for(tokens)) { m->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
 }
 
+// Partials are kept per 16-row block: 16 x D accumulators in the lane order the MFMA leaves them in, and (m, l) per row.
 static int ensure_partials(das_model *m, size_t rows) {
     if (rows <= m->part_rows_cap) return DAS_OK;
     HIPCHK(hipStreamSynchronize(m->st));
     size_t cap = std::max(rows, m->part_rows_cap * 2);
-    if (m->part_acc) { (void)hipFree(m->part_acc); (void)hipFree(m->part_ml); m->part_acc = nullptr; m->part_ml = nullptr; m->part_rows_cap = 0; }
-    hipError_t e1 = hipMalloc((void **)&m->part_acc, cap * m->dm.Hkv * m->dm.D * sizeof(float));
-    hipError_t e2 = hipMalloc((void **)&m->part_ml, cap * m->dm.Hkv * 2 * sizeof(float));
+    if (m->part_o) { (void)hipFree(m->part_o); (void)hipFree(m->part_ml); m->part_o = nullptr; m->part_ml = nullptr; m->part_rows_cap = 0; }
+    hipError_t e1 = hipMalloc((void **)&m->part_o, cap * m->dm.Hkv * 16 * m->dm.D * sizeof(uint16_t));
+    hipError_t e2 = hipMalloc((void **)&m->part_ml, cap * m->dm.Hkv * 32 * sizeof(float));
     if (e1 != hipSuccess || e2 != hipSuccess) {
         g_dev_err = "hipMalloc(attention partials) failed"; (void)hipGetLastError();
-        if (e1 == hipSuccess) (void)hipFree(m->part_acc);
+        if (e1 == hipSuccess) (void)hipFree(m->part_o);
         if (e2 == hipSuccess) (void)hipFree(m->part_ml);
-        m->part_acc = m->part_ml = nullptr;
+        m->part_o = nullptr; m->part_ml = nullptr;
         return DAS_ERR_NOMEM;
     }
     m->part_rows_cap = cap;
@@ -169,7 +171,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     const int NB = (int)blocks.size();
     int T = 0;
     for (auto &b : blocks) T += b.n;
-    std::vector<int> items[3];
+    std::vector<int> items[3], mblk;
     size_t prow = 0;
     // ---- pack the metadata
     int *p = m->h_stage;
@@ -190,7 +192,8 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         const int R = dm.G * pb.n, nrb = (R + 15) / 16;
         const int nchunk = (pb.start + pb.n + DAS_ATTN_CHUNK - 1) / DAS_ATTN_CHUNK;
         b_prow[b] = (int)prow; b_nchunk[b] = nchunk;
-        prow += (size_t)nchunk * R;
+        prow += (size_t)nchunk * nrb;
+        for (int rb = 0; rb < nrb; ++rb) { mblk.push_back(b); mblk.push_back(rb); }
         // two kernel shapes: up to 8 row blocks of 16 query rows per KV head (2 per wave), or up to 16 (4 per wave).
         // One launch for everything up to 8 blocks lets short sequences fill the tail of the long ones.
         const int cls = nrb <= 8 ? 1 : 2;
@@ -214,6 +217,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     }
     int *item_ptr[3];
     for (int c = 0; c < 3; ++c) { item_ptr[c] = p; std::copy(items[c].begin(), items[c].end(), p); p += items[c].size(); }
+    int *mblk_p = p; std::copy(mblk.begin(), mblk.end(), p); p += mblk.size();
     const int n_upd = (int)m->pending_upd.size() / 2;
     int *upd = p; std::copy(m->pending_upd.begin(), m->pending_upd.end(), p); p += 2 * n_upd;
     float *ua = reinterpret_cast<float *>(p);
@@ -232,6 +236,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     pm.tok = dptr(tok); pm.row_pos = dptr(row_pos); pm.row_b = dptr(row_b); pm.sel = dptr(sel); pm.n_sel = n_sel;
     pm.b_slot = dptr(b_slot); pm.b_start = dptr(b_start); pm.b_n = dptr(b_n); pm.b_row0 = dptr(b_row0);
     pm.b_prow = dptr(b_prow); pm.b_nchunk = dptr(b_nchunk);
+    pm.mblk = dptr(mblk_p); pm.n_mblk = (int)mblk.size() / 2;
     pm.page_table = m->page_table; pm.max_pages = m->max_pages; pm.num_pages = (int)m->cfg.num_pages;
     {
         ProfScope ps(m, KC_META);
@@ -250,9 +255,9 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)
-                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_hi, m->q_lo, kl, vl, m->part_acc, m->part_ml, dm, st);
+                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_hi, m->q_lo, kl, vl, m->part_o, m->part_ml, dm, st);
         }
-        { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_acc, m->part_ml, m->attn, dm, st); }
+        { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_o, m->part_ml, m->attn, dm, st); }
         { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st); }
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g2, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
         { ProfScope ps(m, KC_GEMM_GATEUP); launch_gemm(EPI_SILU_FRAG, m->xn, w.wgu, m->act, T, 2 * dm.Fp, dm.d, dm.Fp, st); }
@@ -293,7 +298,7 @@ extern "C" int das_model_free(das_model *m) {
     if (!m) return DAS_ERR_INVALID;
     (void)hipStreamSynchronize(m->st);
     for (void *p : m->allocs) (void)hipFree(p);
-    if (m->part_acc) (void)hipFree(m->part_acc);
+    if (m->part_o) (void)hipFree(m->part_o);
     if (m->part_ml) (void)hipFree(m->part_ml);
     if (m->h_stage) (void)hipHostFree(m->h_stage);
     if (m->h_out) (void)hipHostFree(m->h_out);
@@ -377,6 +382,7 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     // ---- staging
     const size_t max_items = (size_t)c.max_seqs * (c.max_ctx / DAS_ATTN_CHUNK + 2);
     m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)c.max_seqs + 2 * max_items +
+                    2 * ((size_t)c.max_rows * dm.G / 16 + (size_t)c.max_seqs) +
                     2 * ((size_t)c.max_rows / DAS_PAGE + 2 * (size_t)c.max_seqs + 2) + 64;
     HIPCHK(hipHostMalloc((void **)&m->h_stage, m->stage_ints * sizeof(int), hipHostMallocDefault));
     A(m->d_stage, m->stage_ints);

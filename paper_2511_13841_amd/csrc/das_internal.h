@@ -63,8 +63,10 @@ struct PassMeta {
     const int *b_start;    // [NB] first position of the block (= committed length)
     const int *b_n;        // [NB] rows of the block
     const int *b_row0;     // [NB] first row of the block
-    const int *b_prow;     // [NB] base row in the split-KV partial buffers
+    const int *b_prow;     // [NB] base 16-row block in the split-KV partial buffers
     const int *b_nchunk;   // [NB] split-KV chunks
+    const int *mblk;       // [n_mblk][2] (block, 16-row block) pairs: one merge workgroup each per KV head
+    int n_mblk;
     const int *sel;        // [n_sel] rows that get logits
     int n_sel;
     const int *page_table; // [max_seqs][max_pages]
@@ -90,9 +92,9 @@ void launch_rope_kv(const PassMeta &pm, const float *qkv, bf16_t *q_hi, bf16_t *
 void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st);
 // split-KV partial attention for the items of one row-block class, then the merge
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
-                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, float *part_acc, float *part_ml,
+                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, uint16_t *part_o, float *part_ml,
                  const DasDims &dm, hipStream_t st);
-void launch_attn_merge(const PassMeta &pm, const float *part_acc, const float *part_ml, bf16_t *out_frag,
+void launch_attn_merge(const PassMeta &pm, const uint16_t *part_o, const float *part_ml, bf16_t *out_frag,
                        const DasDims &dm, hipStream_t st);
 void launch_argmax(const float *logits, int n_rows, int V, int *out, hipStream_t st);
 void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const int *tok, int NB,

@@ -21,6 +21,18 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// two floats -> packed fp16 pair (round to nearest even), and back
+__device__ __forceinline__ uint32_t pack_h2(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+    h2 v = {(_Float16)a, (_Float16)b};
+    return *reinterpret_cast<uint32_t *>(&v);
+}
+__device__ __forceinline__ float2 unpack_h2(uint32_t u) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+    h2 v = *reinterpret_cast<h2 *>(&u);
+    return make_float2((float)v[0], (float)v[1]);
+}
+
 // 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at
 // lds_wave_base + 16*l.  Inline assembly, so that the copies are ordered only by the explicit
 // s_waitcnt/s_barrier of the tile loop (M0 carries the LDS address; 1 wait state before its use).
@@ -37,7 +49,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
                                                            const bf16_t *__restrict__ q_lo,
                                                            const bf16_t *__restrict__ kpool,
                                                            const bf16_t *__restrict__ vpool,
-                                                           float *__restrict__ part_acc, float *__restrict__ part_ml,
+                                                           uint16_t *__restrict__ part_o, float *__restrict__ part_ml,
                                                            int Hkv, int G, int qstride, float scale_log2e) {
     constexpr int KFR = D / 32;            // K fragments (1 KiB) per page
     constexpr int VDB = D / 16;            // V dim blocks (512 B) per page
@@ -118,36 +130,41 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         }
     };
 
-    auto compute = [&](int ti, const unsigned char *cur) {
-        const int tile_tok0 = tok_begin + ti * DAS_ATTN_TILE;
-        // S^T = K Q^T : s[i][pg][r] = score of token 16*pg + 4*(lane/16) + r for query row lane%16
-        f32x4 s[RBW][2];
+    // ---- the three phases of a tile, kept apart so that two tiles can be interleaved below
+    struct Scores { f32x4 v[RBW][2]; };
+    struct Probs { bf16x8 hi[RBW], lo[RBW]; };
+
+    // S^T = K Q^T : s[i][pg][r] = score of token 16*pg + 4*(lane/16) + r for query row lane%16
+    auto qk = [&](const unsigned char *cur, Scores &s) {
 #pragma unroll
-        for (int i = 0; i < RBW; ++i) { s[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+        for (int i = 0; i < RBW; ++i) { s.v[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s.v[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int ks = 0; ks < KFR; ++ks) {
             const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(cur + (ks * 64 + lane) * 16);
             const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
 #pragma unroll
             for (int i = 0; i < RBW; ++i) {
-                s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s[i][0], 0, 0, 0);
-                s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s[i][1], 0, 0, 0);
-                s[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[i][ks], s[i][0], 0, 0, 0);
-                s[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[i][ks], s[i][1], 0, 0, 0);
+                s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s.v[i][0], 0, 0, 0);
+                s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s.v[i][1], 0, 0, 0);
+                s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[i][ks], s.v[i][0], 0, 0, 0);
+                s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[i][ks], s.v[i][1], 0, 0, 0);
             }
         }
+    };
+
+    // Softmax with a lazily updated reference: p = exp2(s - m_ref).  m_ref only moves when the row's maximum
+    // in this tile exceeds it by more than 8 (a factor 256), which after a row's first tile almost never
+    // happens: the common path needs no cross-lane step and no rescaling of the accumulators.  The decision is
+    // taken per ROW (from the row's own maximum), so a row's arithmetic never depends on its neighbours;
+    // softmax is shift-invariant, the result is exact.  Probabilities leave as two bf16 terms.
+    auto softmax = [&](int ti, const Scores &s, Probs &p) {
+        const int tile_tok0 = tok_begin + ti * DAS_ATTN_TILE;
         const bool need_mask = tile_tok0 + DAS_ATTN_TILE - 1 > ctx;
-        bf16x8 pf[RBW], pl[RBW];               // probabilities as two bf16 terms as well
 #pragma unroll
         for (int i = 0; i < RBW; ++i) {
-            // Softmax with a lazily updated reference: p = exp2(s - m_ref).  m_ref only moves when the row's
-            // maximum in this tile exceeds it by more than 8 (a factor 256), which after a row's first tile
-            // almost never happens: the common path needs no cross-lane step and no rescaling of the
-            // accumulators.  The decision is taken per ROW (from the row's own maximum), so a row's
-            // arithmetic never depends on its neighbours; softmax is shift-invariant, the result is exact.
             float sv[8];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) { sv[r] = s[i][0][r] * scale_log2e; sv[4 + r] = s[i][1][r] * scale_log2e; }
+            for (int r = 0; r < 4; ++r) { sv[r] = s.v[i][0][r] * scale_log2e; sv[4 + r] = s.v[i][1][r] * scale_log2e; }
             if (need_mask) {
                 const int pbase = tile_tok0 + 4 * (lane >> 4);
 #pragma unroll
@@ -180,11 +197,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             l_run[i] += ps;
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                pf[i][r] = (__bf16)pv[r];
-                pl[i][r] = (__bf16)(pv[r] - (float)pf[i][r]);
+                p.hi[i][r] = (__bf16)pv[r];
+                p.lo[i][r] = (__bf16)(pv[r] - (float)p.hi[i][r]);
             }
         }
-        // O^T += V^T P^T : A = V fragment (dims x 32 token slots), B = probabilities
+    };
+
+    // O^T += V^T P^T : A = V fragment (dims x 32 token slots), B = probabilities
+    auto pv = [&](const unsigned char *cur, const Probs &p) {
 #pragma unroll
         for (int db = 0; db < VDB; ++db) {
             const uint2 lo = *reinterpret_cast<const uint2 *>(cur + 2 * PAGE_B + (db * 64 + lane) * 8);
@@ -192,52 +212,74 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
             const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
 #pragma unroll
-            for (int i = 0; i < RBW; ++i)
-            {
-                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[i], acc[i][db], 0, 0, 0);
-                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl[i], acc[i][db], 0, 0, 0);
+            for (int i = 0; i < RBW; ++i) {
+                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.hi[i], acc[i][db], 0, 0, 0);
+                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.lo[i], acc[i][db], 0, 0, 0);
             }
         }
     };
 
-    // Tile ti lives in stage ti % NS.  At the top of an iteration the copies of tile ti have landed for
-    // every wave (only the NS-2 newer tiles may still be in flight) and every wave is done with tile
-    // ti-1, whose stage is then refilled with tile ti+NS-1.  Copies are issued unconditionally (past the
-    // end: the last tile again, into a stage nobody reads) so that the wait is the same in every iteration.
-    const int last = ntiles - 1;
-#pragma unroll
-    for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(s0, last), s0);
+    // Two tiles per iteration.  Stage ring of NS = 4: tiles ti and ti+1 have landed for every wave (vmcnt(0)
+    // before the barrier) and every wave is done with tiles ti-2 and ti-1, whose stages are refilled with
+    // ti+2 and ti+3 while this pair is processed.  The score MFMAs of the second tile are issued before the
+    // softmax of the first, so that the matrix pipe works under the exp/convert arithmetic of the same wave.
+    // Per row the order of operations is that of one tile after the other.
+    static_assert(NS == 4, "two tiles in use, two in flight");
+    issue(0, 0);
+    if (ntiles > 1) issue(1, 1);
     int stage = 0;
-    for (int ti = 0; ti < ntiles; ++ti) {
-        __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD));       // vmcnt only (expcnt, lgkmcnt: no wait)
-        __builtin_amdgcn_s_barrier();      // bare barrier: a fence here would drain the copies in flight
+    for (int ti = 0; ti < ntiles; ti += 2) {
+        __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0)
+        __builtin_amdgcn_s_barrier();          // bare barrier: no fence needed, LDS is written by the copies only
         asm volatile("" ::: "memory");
-        issue(min(ti + NS - 1, last), stage == 0 ? NS - 1 : stage - 1);
-        if (any_active) compute(ti, smem + stage * TILE_B);
-        stage = stage == NS - 1 ? 0 : stage + 1;
+        if (ti + 2 < ntiles) issue(ti + 2, stage ^ 2);
+        if (ti + 3 < ntiles) issue(ti + 3, (stage ^ 2) + 1);
+        if (any_active) {
+            const unsigned char *c0 = smem + stage * TILE_B, *c1 = smem + (stage + 1) * TILE_B;
+            const bool two = ti + 1 < ntiles;
+            Scores s0, s1;
+            Probs p0, p1;
+            qk(c0, s0);
+            if (two) qk(c1, s1);
+            softmax(ti, s0, p0);
+            pv(c0, p0);
+            if (two) {
+                softmax(ti + 1, s1, p1);
+                pv(c1, p1);
+            }
+        }
+        stage ^= 2;
     }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
-    // ---- partial results: (m, l) per row and the un-normalised accumulator
+    // ---- partial results per 16-row block: (m, l) per row in fp32 and the chunk's normalised output acc / l in
+    // fp16 (values bounded by the largest |v|; 11 significant bits, well below the bf16 rounding of the merged
+    // result), in the lane order the accumulators are held in: dim blocks 2q and 2q+1 share one 16-byte store, a
+    // contiguous KiB per instruction.  HBM writes cost this kernel about three times their bytes in read
+    // bandwidth, hence the narrow format.
+    const int nrb = (R + 15) >> 4;
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
         float l = l_run[i];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        const int rr = (wave * RBW + i) * 16 + (lane & 15);
-        if (rr < R) {
-            const size_t id = ((size_t)pm.b_prow[b] + (size_t)chunk * R + rr) * Hkv + kvh;
-            if ((lane >> 4) == 0) { part_ml[2 * id] = m_run[i]; part_ml[2 * id + 1] = l; }
-            float *dst = part_acc + id * D + 4 * (lane >> 4);
+        const int rb = wave * RBW + i;
+        if (rb < nrb) {
+            const size_t id = ((size_t)pm.b_prow[b] + (size_t)chunk * nrb + rb) * Hkv + kvh;
+            if ((lane >> 4) == 0) *reinterpret_cast<float2 *>(part_ml + id * 32 + 2 * lane) = make_float2(m_run[i], l);
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            uint4 *dst = reinterpret_cast<uint4 *>(part_o + id * (16 * D)) + lane;
 #pragma unroll
-            for (int db = 0; db < VDB; ++db)
-                *reinterpret_cast<float4 *>(dst + 16 * db) = make_float4(acc[i][db][0], acc[i][db][1], acc[i][db][2], acc[i][db][3]);
+            for (int q = 0; q < VDB / 2; ++q) {
+                const f32x4 lo = acc[i][2 * q] * inv, hi = acc[i][2 * q + 1] * inv;
+                dst[q * 64] = make_uint4(pack_h2(lo[0], lo[1]), pack_h2(lo[2], lo[3]), pack_h2(hi[0], hi[1]), pack_h2(hi[2], hi[3]));
+            }
         }
     }
 }
 
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
-                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, float *part_acc, float *part_ml,
+                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, uint16_t *part_o, float *part_ml,
                  const DasDims &dm, hipStream_t st) {
     if (n_items <= 0) return;
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
@@ -246,7 +288,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
     // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
 #define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_acc, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
     if (dm.D == 128) {
         if (rbw <= 2) ATTN_LAUNCH(128, 1); else ATTN_LAUNCH(128, 2);
@@ -257,46 +299,69 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
 }
 
 // ---------------------------------------------------------------- merge of the chunk partials
-// grid (T, Hq), block 64; ascending chunk order, fp32.  Output: bf16, fragment order, K = Hq*D.
+// One wave per (sequence, 16-row block, KV head, pair of dim blocks): lane l holds row l%16 and dims
+// 16*db + 4*(l/16) .. +3 of its two dim blocks, as the attention kernel left them.  A chunk contributes its
+// normalised output with weight l * 2^(m - M); ascending chunk order, fp32; chunks a row cannot see carry
+// m = -inf and are skipped.  Output: bf16, fragment order, K = Hq*D.
 template <int D>
-__global__ __launch_bounds__(64) void attn_merge_kernel(PassMeta pm, const float *__restrict__ part_acc,
+__global__ __launch_bounds__(64) void attn_merge_kernel(PassMeta pm, const uint16_t *__restrict__ part_o,
                                                         const float *__restrict__ part_ml, bf16_t *__restrict__ out,
                                                         int Hq, int Hkv, int G) {
-    constexpr int E = D / 64;
-    const int t = blockIdx.x, a = blockIdx.y, lane = threadIdx.x;
-    const int b = pm.row_b[t];
-    const int j = t - pm.b_row0[b];
-    const int kvh = a / G, g = a % G;
-    const int R = G * pm.b_n[b], rr = j * G + g;
-    const int last_chunk = (pm.b_start[b] + j) / DAS_ATTN_CHUNK;     // chunks holding positions <= ctx + j
-    float M = -INFINITY, den = 0.f, num[E];
+    const int b = pm.mblk[2 * blockIdx.x], rb = pm.mblk[2 * blockIdx.x + 1];
+    const int kvh = blockIdx.y, q = blockIdx.z, lane = threadIdx.x;     // this wave: dim blocks 2q and 2q+1
+    const int n = pm.b_n[b];
+    const int R = G * n, nrb = (R + 15) >> 4, nchunk = pm.b_nchunk[b];
+    const int rr = rb * 16 + (lane & 15);
+    float M = -INFINITY, den = 0.f;
+    float num[8];
 #pragma unroll
-    for (int e = 0; e < E; ++e) num[e] = 0.f;
-    for (int c = 0; c <= last_chunk; ++c) {
-        const size_t id = ((size_t)pm.b_prow[b] + (size_t)c * R + rr) * Hkv + kvh;
-        const float mc = part_ml[2 * id], lc = part_ml[2 * id + 1];
-        if (mc == -INFINITY) continue;
-        const float mn = fmaxf(M, mc);
-        const float a0 = exp2f(M - mn), a1 = exp2f(mc - mn);
-        den = den * a0 + lc * a1;
+    for (int e = 0; e < 8; ++e) num[e] = 0.f;
+    const size_t id0 = ((size_t)pm.b_prow[b] + rb) * Hkv + kvh, idstep = (size_t)nrb * Hkv;
+    auto load = [&](int c, float2 &ml, uint4 &v) {
+        const size_t id = id0 + (size_t)c * idstep;
+        ml = *reinterpret_cast<const float2 *>(part_ml + id * 32 + 2 * (lane & 15));
+        v = (reinterpret_cast<const uint4 *>(part_o + id * (16 * D)) + q * 64)[lane];
+    };
+    float2 ml_n;
+    uint4 v_n;
+    load(0, ml_n, v_n);
+    for (int c = 0; c < nchunk; ++c) {
+        const float2 ml = ml_n;
+        const uint4 v = v_n;
+        if (c + 1 < nchunk) load(c + 1, ml_n, v_n);        // next chunk's loads fly while this one is merged
+        if (ml.x == -INFINITY) continue;
+        const float mn = fmaxf(M, ml.x);
+        const float a0 = exp2f(M - mn), a1 = ml.y * exp2f(ml.x - mn);
+        den = den * a0 + a1;
+        const float2 o0 = unpack_h2(v.x), o1 = unpack_h2(v.y), o2 = unpack_h2(v.z), o3 = unpack_h2(v.w);
+        const float o[8] = {o0.x, o0.y, o1.x, o1.y, o2.x, o2.y, o3.x, o3.y};
 #pragma unroll
-        for (int e = 0; e < E; ++e) num[e] = num[e] * a0 + part_acc[id * D + lane * E + e] * a1;
+        for (int e = 0; e < 8; ++e) num[e] = num[e] * a0 + o[e] * a1;
         M = mn;
     }
+    if (rr >= R) return;
+    const int j = rr / G, g = rr % G;
+    const int t = pm.b_row0[b] + j, a = kvh * G + g;
     const float inv = 1.f / den;
     const int K = Hq * D;
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const float v = num[e] * inv;
-        uint32_t u = __float_as_uint(v);
+    auto rne = [](float f) -> uint32_t {
+        uint32_t u = __float_as_uint(f);
         u += 0x7FFFu + ((u >> 16) & 1u);
-        out[frag_off(t, a * D + lane * E + e, K)] = (bf16_t)(u >> 16);
+        return u >> 16;
+    };
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        // four consecutive dims: they share one 8-element group of the fragment layout
+        const uint32_t lo = rne(num[4 * h] * inv) | (rne(num[4 * h + 1] * inv) << 16);
+        const uint32_t hi = rne(num[4 * h + 2] * inv) | (rne(num[4 * h + 3] * inv) << 16);
+        *reinterpret_cast<uint2 *>(out + frag_off(t, a * D + 16 * (2 * q + h) + 4 * (lane >> 4), K)) = make_uint2(lo, hi);
     }
 }
 
-void launch_attn_merge(const PassMeta &pm, const float *part_acc, const float *part_ml, bf16_t *out_frag,
+void launch_attn_merge(const PassMeta &pm, const uint16_t *part_o, const float *part_ml, bf16_t *out_frag,
                        const DasDims &dm, hipStream_t st) {
-    dim3 g(pm.T, dm.Hq), blk(64);
-    if (dm.D == 128) attn_merge_kernel<128><<<g, blk, 0, st>>>(pm, part_acc, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
-    else attn_merge_kernel<64><<<g, blk, 0, st>>>(pm, part_acc, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
+    if (pm.n_mblk <= 0) return;
+    dim3 g(pm.n_mblk, dm.Hkv, dm.D / 32), blk(64);
+    if (dm.D == 128) attn_merge_kernel<128><<<g, blk, 0, st>>>(pm, part_o, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
+    else attn_merge_kernel<64><<<g, blk, 0, st>>>(pm, part_o, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
 }
