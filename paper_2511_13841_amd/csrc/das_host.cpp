@@ -204,15 +204,19 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         }
     }
     if (prow > 0x7FFFFFFFull) return DAS_ERR_NOMEM;
-    // longest work items first, so that the short last chunks fill the tail of the launch
+    // One work item per (sequence, chunk, KV head), longest first over the whole launch so that the short last
+    // chunks fill its tail; among equal lengths one KV head's items run side by side (measured faster than the
+    // heads of one chunk side by side).  Entry: sequence, chunk | head << 20.
     for (int c = 0; c < 3; ++c) {
         std::vector<std::pair<int, int>> v;
-        for (size_t i = 0; i + 1 < items[c].size(); i += 2) v.push_back({items[c][i], items[c][i + 1]});
+        for (int h = 0; h < dm.Hkv; ++h)
+            for (size_t i = 0; i + 1 < items[c].size(); i += 2) v.push_back({items[c][i], items[c][i + 1] | (h << 20)});
         auto tokens = [&](const std::pair<int, int> &it) {
             const int total = blocks[it.first].start + blocks[it.first].n;
-            return std::min(total - it.second * DAS_ATTN_CHUNK, DAS_ATTN_CHUNK);
+            return std::min(total - (it.second & 0xFFFFF) * DAS_ATTN_CHUNK, DAS_ATTN_CHUNK);
         };
         std::stable_sort(v.begin(), v.end(), [&](const std::pair<int, int> &a, const std::pair<int, int> &b) { return tokens(a) > tokens(b); });
+        items[c].resize(2 * v.size());
         for (size_t i = 0; i < v.size(); ++i) { items[c][2 * i] = v[i].first; items[c][2 * i + 1] = v[i].second; }
     }
     int *item_ptr[3];
@@ -381,7 +385,7 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     HIPCHK(hipMemsetAsync(m->xsel, 0, Mp * d * 2, m->st));
     // ---- staging
     const size_t max_items = (size_t)c.max_seqs * (c.max_ctx / DAS_ATTN_CHUNK + 2);
-    m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)c.max_seqs + 2 * max_items +
+    m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)c.max_seqs + 2 * max_items * dm.Hkv +
                     2 * ((size_t)c.max_rows * dm.G / 16 + (size_t)c.max_seqs) +
                     2 * ((size_t)c.max_rows / DAS_PAGE + 2 * (size_t)c.max_seqs + 2) + 64;
     HIPCHK(hipHostMalloc((void **)&m->h_stage, m->stage_ints * sizeof(int), hipHostMallocDefault));

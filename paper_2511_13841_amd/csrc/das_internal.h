@@ -22,7 +22,7 @@
 typedef uint16_t bf16_t;   // raw bf16 bit pattern in memory
 
 #define DAS_PAGE 16
-#define DAS_ATTN_CHUNK 1024          // tokens per split-KV work item (absolute-position aligned)
+#define DAS_ATTN_CHUNK 2048          // tokens per split-KV work item (absolute-position aligned)
 #define DAS_ATTN_TILE 32             // tokens per inner tile = 2 pages
 
 enum DasKernelClass {

@@ -64,9 +64,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     __shared__ __align__(16) unsigned char smem[NS * TILE_B];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
-    // items fastest in dispatch order (measured faster than running a chunk's KV heads side by side)
-    const int b = items[2 * blockIdx.x], chunk = items[2 * blockIdx.x + 1];
-    const int kvh = blockIdx.y;
+    // work items arrive sorted longest first: sequence, chunk | KV head << 20
+    const int b = items[2 * blockIdx.x], chunk = items[2 * blockIdx.x + 1] & 0xFFFFF;
+    const int kvh = items[2 * blockIdx.x + 1] >> 20;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ctx = pm.b_start[b], n = pm.b_n[b], row0 = pm.b_row0[b];
     const int R = G * n;
@@ -117,9 +117,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     // ---- tile loader: 16-byte unit u of the tile belongs to segment u / UNITS_PER_SEG
     auto issue = [&](int ti, int stage) {
         // pages 2*ti and 2*ti+1 of the chunk (the second one was clamped to the last page at load)
-        static_assert(NPREG == 1, "one register of 64 page ids covers a chunk");
-        const int pg0 = __builtin_amdgcn_readlane(my_page[0], 2 * ti);
-        const int pg1 = __builtin_amdgcn_readlane(my_page[0], 2 * ti + 1);
+        static_assert(NPREG <= 2, "at most two registers of 64 page ids per chunk");
+        const int li = (2 * ti) & 63;
+        int pg0 = __builtin_amdgcn_readlane(my_page[0], li), pg1 = __builtin_amdgcn_readlane(my_page[0], li + 1);
+        if (NPREG == 2) {
+            const int qg0 = __builtin_amdgcn_readlane(my_page[NPREG - 1], li), qg1 = __builtin_amdgcn_readlane(my_page[NPREG - 1], li + 1);
+            if (2 * ti >= 64) { pg0 = qg0; pg1 = qg1; }
+        }
 #pragma unroll
         for (int jn = 0; jn < NLOAD; ++jn) {
             const int u = tid + jn * NT;
@@ -152,30 +156,29 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         }
     };
 
-    // Softmax with a lazily updated reference: p = exp2(s - m_ref).  m_ref only moves when the row's maximum
-    // in this tile exceeds it by more than 8 (a factor 256), which after a row's first tile almost never
+    // Softmax with a lazily updated reference: p = exp2(s * scale - m_ref).  m_ref only moves when the row's
+    // maximum in this tile exceeds it by more than 8 (a factor 256), which after a row's first tile almost never
     // happens: the common path needs no cross-lane step and no rescaling of the accumulators.  The decision is
     // taken per ROW (from the row's own maximum), so a row's arithmetic never depends on its neighbours;
-    // softmax is shift-invariant, the result is exact.  Probabilities leave as two bf16 terms.
-    auto softmax = [&](int ti, const Scores &s, Probs &p) {
+    // softmax is shift-invariant, the result is exact.
+    // row_check: causal mask (only the chunk's last tiles need one), row maximum, and the rare move of m_ref.
+    auto row_check = [&](int ti, Scores &s) {
         const int tile_tok0 = tok_begin + ti * DAS_ATTN_TILE;
         const bool need_mask = tile_tok0 + DAS_ATTN_TILE - 1 > ctx;
 #pragma unroll
         for (int i = 0; i < RBW; ++i) {
-            float sv[8];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) { sv[r] = s.v[i][0][r] * scale_log2e; sv[4 + r] = s.v[i][1][r] * scale_log2e; }
             if (need_mask) {
                 const int pbase = tile_tok0 + 4 * (lane >> 4);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    if (pbase + r > lim[i]) sv[r] = -INFINITY;
-                    if (pbase + 16 + r > lim[i]) sv[4 + r] = -INFINITY;
+                    if (pbase + r > lim[i]) s.v[i][0][r] = -INFINITY;
+                    if (pbase + 16 + r > lim[i]) s.v[i][1][r] = -INFINITY;
                 }
             }
-            float mt = sv[0];
+            float mt = fmaxf(s.v[i][0][0], s.v[i][1][0]);
 #pragma unroll
-            for (int r = 1; r < 8; ++r) mt = fmaxf(mt, sv[r]);
+            for (int r = 1; r < 4; ++r) mt = fmaxf(mt, fmaxf(s.v[i][0][r], s.v[i][1][r]));
+            mt *= scale_log2e;
             if (__any(mt > m_run[i] + 8.f)) {          // some row of this block may have to move its reference
                 mt = fmaxf(mt, __shfl_xor(mt, 16));
                 mt = fmaxf(mt, __shfl_xor(mt, 32));    // the row's maximum, same in its four lanes
@@ -189,17 +192,39 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
                     for (int db = 0; db < VDB; ++db) acc[i][db] *= alpha;
                 }
             }
+        }
+    };
+    // probabilities of a checked tile, as two bf16 terms (p = hi + lo to ~16 bits), and the row sums
+    auto probs = [&](const Scores &s, Probs &p) {
+#pragma unroll
+        for (int i = 0; i < RBW; ++i) {
             const float ms = (m_run[i] == -INFINITY) ? 0.f : m_run[i];
             float ps = 0.f;
             float pv[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) { pv[r] = __builtin_amdgcn_exp2f(sv[r] - ms); ps += pv[r]; }
-            l_run[i] += ps;
-#pragma unroll
             for (int r = 0; r < 8; ++r) {
-                p.hi[i][r] = (__bf16)pv[r];
-                p.lo[i][r] = (__bf16)(pv[r] - (float)p.hi[i][r]);
+                pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s.v[i][r >> 2][r & 3], scale_log2e, -ms));
+                ps += pv[r];
             }
+            l_run[i] += ps;
+            // p = hi + lo: round a pair to bf16 with one packed conversion, widen the two halves again by
+            // shift / mask, and convert the remainders the same way
+            uint32_t hu[4], lu[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                typedef __attribute__((ext_vector_type(2))) float f32x2;
+                typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+                const bf16x2 h = __builtin_convertvector((f32x2){pv[2 * r], pv[2 * r + 1]}, bf16x2);
+                hu[r] = *reinterpret_cast<const uint32_t *>(&h);
+                const float ra = pv[2 * r] - __uint_as_float(hu[r] << 16);
+                const float rb = pv[2 * r + 1] - __uint_as_float(hu[r] & 0xFFFF0000u);
+                const bf16x2 l = __builtin_convertvector((f32x2){ra, rb}, bf16x2);
+                lu[r] = *reinterpret_cast<const uint32_t *>(&l);
+            }
+            typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+            const u32x4 hv = {hu[0], hu[1], hu[2], hu[3]}, lv = {lu[0], lu[1], lu[2], lu[3]};
+            p.hi[i] = *reinterpret_cast<const bf16x8 *>(&hv);
+            p.lo[i] = *reinterpret_cast<const bf16x8 *>(&lv);
         }
     };
 
@@ -207,9 +232,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     auto pv = [&](const unsigned char *cur, const Probs &p) {
 #pragma unroll
         for (int db = 0; db < VDB; ++db) {
-            const uint2 lo = *reinterpret_cast<const uint2 *>(cur + 2 * PAGE_B + (db * 64 + lane) * 8);
-            const uint2 hi = *reinterpret_cast<const uint2 *>(cur + 3 * PAGE_B + (db * 64 + lane) * 8);
-            uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            // the two halves of a fragment (tokens of the first and of the second page) are read by separate
+            // 8-byte loads straight into its registers; left to itself the compiler pairs the loads of
+            // neighbouring dim blocks instead and pays for it with register moves
+            typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+            typedef const volatile __attribute__((address_space(3))) u32x2 *lds_u32x2_ptr;
+            const u32x2 lo = *(lds_u32x2_ptr)(cur + 2 * PAGE_B + (db * 64 + lane) * 8);
+            const u32x2 hi = *(lds_u32x2_ptr)(cur + 3 * PAGE_B + (db * 64 + lane) * 8);
+            typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+            u32x4 vv = {lo[0], lo[1], hi[0], hi[1]};
             const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
 #pragma unroll
             for (int i = 0; i < RBW; ++i) {
@@ -219,11 +250,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         }
     };
 
-    // Two tiles per iteration.  Stage ring of NS = 4: tiles ti and ti+1 have landed for every wave (vmcnt(0)
-    // before the barrier) and every wave is done with tiles ti-2 and ti-1, whose stages are refilled with
-    // ti+2 and ti+3 while this pair is processed.  The score MFMAs of the second tile are issued before the
-    // softmax of the first, so that the matrix pipe works under the exp/convert arithmetic of the same wave.
-    // Per row the order of operations is that of one tile after the other.
+    // Two tiles per barrier.  Stage ring of NS = 4: tiles ti and ti+1 have landed for every wave (vmcnt(0) before
+    // the barrier) and every wave is done with tiles ti-2 and ti-1, whose stages are refilled with ti+2 and ti+3
+    // while this pair is processed.  (Matrix and vector instructions of one SIMD do not overlap on this chip --
+    // measured: their times add even with four waves per SIMD -- so nothing is gained by interleaving the score
+    // MFMAs of one tile with the exponentials of another; what counts is the instruction count per tile.)
     static_assert(NS == 4, "two tiles in use, two in flight");
     issue(0, 0);
     if (ntiles > 1) issue(1, 1);
@@ -236,16 +267,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         if (ti + 3 < ntiles) issue(ti + 3, (stage ^ 2) + 1);
         if (any_active) {
             const unsigned char *c0 = smem + stage * TILE_B, *c1 = smem + (stage + 1) * TILE_B;
-            const bool two = ti + 1 < ntiles;
-            Scores s0, s1;
-            Probs p0, p1;
+            Scores s0;
+            Probs p0;
             qk(c0, s0);
-            if (two) qk(c1, s1);
-            softmax(ti, s0, p0);
+            row_check(ti, s0);
+            probs(s0, p0);
             pv(c0, p0);
-            if (two) {
-                softmax(ti + 1, s1, p1);
-                pv(c1, p1);
+            if (ti + 1 < ntiles) {
+                qk(c1, s0);
+                row_check(ti + 1, s0);
+                probs(s0, p0);
+                pv(c1, p0);
             }
         }
         stage ^= 2;
@@ -283,7 +315,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
                  const DasDims &dm, hipStream_t st) {
     if (n_items <= 0) return;
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
-    dim3 g(n_items, dm.Hkv), blk(256);
+    dim3 g(n_items);
     const size_t lds = 0;     // tile stages are static LDS arrays
     // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
     // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
