@@ -8,5 +8,5 @@ with controlled acceptance and keyed uniform streams.
 from .gen import (build, weight_count, weights_bf16, bf16_to_f32, f32_to_bf16,
                   kv_synth, uniforms, num_threads)
 from .workloads import (ModelShape, Workload, MODELS, WORKLOADS, workload,
-                        context_lengths, draft_budgets, prompts, make_drafts,
+                        context_lengths, draft_budgets, max_budget, prompts, make_drafts,
                         expected_accept_len)

@@ -107,10 +107,8 @@ def draft_budgets(wl, ctx_lens):
     """Per-sequence draft budget k_i from the current lengths (int32[B])."""
     c = np.asarray(ctx_lens, dtype=np.int64)
     r = wl.budgets
-    if r == "k4":
-        return np.full(c.shape, 4, np.int32)
-    if r == "k16":
-        return np.full(c.shape, 16, np.int32)
+    if r[0] == "k" and r[1:].isdigit():            # uniform chains: "k4", "k16", ...
+        return np.full(c.shape, int(r[1:]), np.int32)
     if r == "quartile":
         # rank by current length within the batch; shortest quartile -> 2 ... longest -> 16
         order = np.argsort(c, kind="stable")
@@ -122,6 +120,14 @@ def draft_budgets(wl, ctx_lens):
         k = np.floor(32.0 * np.log2(np.maximum(c, 1) / 512.0) / 6.0)
         return np.clip(k, 0, 32).astype(np.int32)
     raise ValueError(r)
+
+
+def max_budget(wl):
+    """Largest k_i the workload's budget recipe can return."""
+    r = wl.budgets
+    if r[0] == "k" and r[1:].isdigit():
+        return int(r[1:])
+    return {"quartile": 16, "loglen": 32}[r]
 
 
 def prompts(lengths, vocab, seed):

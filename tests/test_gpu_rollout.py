@@ -1,0 +1,21 @@
+"""Whole rollouts on the GPU: speculative decoding must emit the tokens of plain decoding (the losslessness
+the paper claims in its abstract and Sec. 5.1) while the batch collapses, in fewer forward passes."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def test_speculative_rollout_equals_plain_rollout_tiny():
+    from paper_2511_13841_amd.rollout_makespan import run
+    r = run(model="tiny", batch=12, max_len=48, accept_p=0.7, k_medium=2, k_long=4, ctx_lo=16, ctx_hi=64, seed=77)
+    assert r["sequences_differing_from_plain_decoding"] == 0
+    assert r["speculative"]["forwards"] < r["plain"]["forwards"]
+    assert r["speculative"]["accepted_drafts"] > 0
+    assert r["plain"]["tokens_processed"] == r["target_len"]["sum"]
+
+
+def test_speculative_rollout_equals_plain_rollout_wide_model_few_layers():
+    from paper_2511_13841_amd.rollout_makespan import run
+    r = run(model="1.5b", batch=6, max_len=24, accept_p=0.8, k_medium=3, k_long=6, ctx_lo=200, ctx_hi=2300, seed=78, n_layers=2)
+    assert r["sequences_differing_from_plain_decoding"] == 0
+    assert r["speculative"]["forwards"] < r["plain"]["forwards"]
