@@ -57,6 +57,8 @@ struct das_model {
     float *h = nullptr, *cs = nullptr, *logits = nullptr, *row_stats = nullptr;
     bf16_t *xn = nullptr, *q_hi = nullptr, *q_lo = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
     float *qkv = nullptr;                  // fp32 projections of the pass: rounded to bf16 once, after RoPE
+    float *gemm_ws = nullptr;        // slice partials of narrow few-row GEMMs
+    size_t gemm_ws_floats = 0;
     uint16_t *part_o = nullptr;      // split-KV partial outputs (fp16, normalised per chunk)
     float *part_ml = nullptr;        // their (m, l) per row
     size_t part_rows_cap = 0;
@@ -254,7 +256,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         const LayerW &w = m->layers[l];
         bf16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
-        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st); }
+        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats); }
         { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->q_hi, m->q_lo, m->cs, kl, vl, dm, st); }
         {
             ProfScope ps(m, KC_ATTN);
@@ -262,14 +264,14 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
                 launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_hi, m->q_lo, kl, vl, m->part_o, m->part_ml, dm, st);
         }
         { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_o, m->part_ml, m->attn, dm, st); }
-        { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st); }
+        { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st, m->gemm_ws, m->gemm_ws_floats); }
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g2, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
-        { ProfScope ps(m, KC_GEMM_GATEUP); launch_gemm(EPI_SILU_FRAG, m->xn, w.wgu, m->act, T, 2 * dm.Fp, dm.d, dm.Fp, st); }
-        { ProfScope ps(m, KC_GEMM_DOWN); launch_gemm(EPI_RESID_F32, m->act, w.wd, m->h, T, dm.d, dm.Fp, dm.d, st); }
+        { ProfScope ps(m, KC_GEMM_GATEUP); launch_gemm(EPI_SILU_FRAG, m->xn, w.wgu, m->act, T, 2 * dm.Fp, dm.d, dm.Fp, st, m->gemm_ws, m->gemm_ws_floats); }
+        { ProfScope ps(m, KC_GEMM_DOWN); launch_gemm(EPI_RESID_F32, m->act, w.wd, m->h, T, dm.d, dm.Fp, dm.d, st, m->gemm_ws, m->gemm_ws_floats); }
     }
     if (n_sel > 0) {
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, m->gf, m->xsel, pm.sel, n_sel, dm.d, dm.rms_eps, st); }
-        { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st); }
+        { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
         { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
     }
     hipError_t le = hipGetLastError();
@@ -379,6 +381,11 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->q_hi, Mp * qd); A(m->q_lo, Mp * qd); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
     A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
     A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs);
+    {   // slice partials of the narrow GEMMs when a pass has at most 512 rows: [slices <= 8][rows][widest narrow output]
+        const size_t n_narrow = std::max<size_t>(std::max<size_t>(dm.qkvN, d), V < 16384 ? V : 0);
+        m->gemm_ws_floats = 8 * std::min<size_t>(512, Mp) * n_narrow;
+        A(m->gemm_ws, m->gemm_ws_floats);
+    }
     HIPCHK(hipMemsetAsync(m->xn, 0, Mp * d * 2, m->st));
     HIPCHK(hipMemsetAsync(m->attn, 0, Mp * qd * 2, m->st));
     HIPCHK(hipMemsetAsync(m->act, 0, Mp * Fp * 2, m->st));
@@ -826,21 +833,24 @@ extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a
     if (M < 1 || N < 1 || K < 8 || (K % 8) || !a || !w || !c) return DAS_ERR_INVALID;
     const int Mp = round_up(M, 256), Np = round_up(N, 256), Kp = round_up(K, 64);
     bf16_t *da = nullptr, *dw = nullptr, *pa = nullptr, *pw = nullptr;
-    float *dc = nullptr;
+    float *dc = nullptr, *dws = nullptr;
     int rc = DAS_OK;
     auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
     do {
         if (bad(hipMalloc((void **)&da, (size_t)M * K * 2)) || bad(hipMalloc((void **)&dw, (size_t)N * K * 2)) ||
             bad(hipMalloc((void **)&pa, (size_t)Mp * Kp * 2)) || bad(hipMalloc((void **)&pw, (size_t)Np * Kp * 2)) ||
             bad(hipMalloc((void **)&dc, (size_t)M * N * 4))) break;
+        int slice_tiles = 0;
+        const size_t ws_floats = M <= 512 ? (size_t)gemm_slices(Kp, &slice_tiles) * M * N : 0;
+        if (ws_floats && bad(hipMalloc((void **)&dws, ws_floats * 4))) break;
         if (bad(hipMemcpy(da, a, (size_t)M * K * 2, hipMemcpyHostToDevice)) || bad(hipMemcpy(dw, w, (size_t)N * K * 2, hipMemcpyHostToDevice))) break;
         launch_pack_weight(da, pa, M, K, Mp, Kp, nullptr);
         launch_pack_weight(dw, pw, N, K, Np, Kp, nullptr);
-        launch_gemm(EPI_F32_ROWMAJOR, pa, pw, dc, M, N, Kp, N, nullptr);
+        launch_gemm(EPI_F32_ROWMAJOR, pa, pw, dc, M, N, Kp, N, nullptr, dws, ws_floats);
         if (bad(hipDeviceSynchronize())) break;
         if (bad(hipMemcpy(c, dc, (size_t)M * N * 4, hipMemcpyDeviceToHost))) break;
     } while (0);
-    (void)hipFree(da); (void)hipFree(dw); (void)hipFree(pa); (void)hipFree(pw); (void)hipFree(dc);
+    (void)hipFree(da); (void)hipFree(dw); (void)hipFree(pa); (void)hipFree(pw); (void)hipFree(dc); (void)hipFree(dws);
     return rc;
 }
 

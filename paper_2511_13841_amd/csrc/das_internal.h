@@ -89,7 +89,10 @@ void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, in
 void launch_rope_kv(const PassMeta &pm, const float *qkv, bf16_t *q_hi, bf16_t *q_lo, const float *cs,
                     bf16_t *kpool_layer, bf16_t *vpool_layer, const DasDims &dm, hipStream_t st);
 // C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
-void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st);
+// ws: fp32 workspace of ws_floats elements for the slice partials of narrow few-row GEMMs (may be null: slower, same result)
+void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
+                 float *ws, size_t ws_floats);
+int gemm_slices(int K, int *slice_tiles);
 // split-KV partial attention for the items of one row-block class, then the merge
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
                  const bf16_t *kpool_layer, const bf16_t *vpool_layer, uint16_t *part_o, float *part_ml,

@@ -30,10 +30,16 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // WGM x WGN waves, each owning TM x TN blocks of 32x32.  A k-tile is KS MFMA k-steps (BK = 16*KS: 64 or 32).  NS LDS stages form a
 // ring: while k-tile kt is multiplied, k-tiles kt+1 .. kt+NS-2 are already in flight and the stage of
 // kt-1 is being refilled with kt+NS-1.
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3)>
+//
+// SL selects how K is summed.  0: one pass over K.  Narrow outputs (QKV, O, down) are DEFINED as a sum of K slices
+// of `slice_tiles` k-tiles, each slice accumulated from zero and the slices added in ascending order, so that few-row
+// launches can spread the slices over workgroups without changing a single bit of the result:
+// 1: this workgroup walks all slices and folds each finished slice into a second set of registers;
+// 2: this workgroup computes slice blockIdx.y and stores the raw fp32 partial to slab blockIdx.y of Cv ([slices][M][ldc]).
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
-                                                             int tiles_m, int tiles_n) {
+                                                             int tiles_m, int tiles_n, int slice_tiles) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int AB = WGM * TM, BB = WGN * TN;          // 32-row blocks per tile
     constexpr int RBU = KS * 64;                          // 16-byte units of one row block in one k-tile
@@ -58,6 +64,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int wm = wave / WGN, wn = wave % WGN;
     const int KF = K >> 4;                                 // fragments per row block
     const int KT = K / (16 * KS);                          // k-tiles
+    const int kt_begin = SL == 2 ? (int)blockIdx.y * slice_tiles : 0;
+    const int kt_end = SL == 2 ? min(KT, kt_begin + slice_tiles) : KT;
+    if (SL == 2) Cv = reinterpret_cast<float *>(Cv) + (size_t)blockIdx.y * M * ldc;
     const uint4 *Ag = reinterpret_cast<const uint4 *>(A);
     const uint4 *Wg = reinterpret_cast<const uint4 *>(W);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem + wave * 1024;
@@ -134,13 +143,33 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 
     // Copies are issued unconditionally (past the end: the last k-tile again, into a stage nobody will read),
     // so "all but the newest NS-2 tiles have landed" is the same s_waitcnt in every iteration.
-    const int last = KT - 1;
+    const int last = kt_end - 1;
 #pragma unroll
-    for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(s0, last), s0);
+    for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(kt_begin + s0, last), s0);
+    f32x16 tot[SL == 1 ? TM : 1][SL == 1 ? TN : 1];      // SL == 1: sum of the finished slices
+    if (SL == 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tot[SL == 1 ? i : 0][SL == 1 ? j : 0][r] = 0.f;
+    }
+    auto fold = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    tot[SL == 1 ? i : 0][SL == 1 ? j : 0][r] += acc[i][j][r];
+                    acc[i][j][r] = 0.f;
+                }
+    };
     // one copy of the whole k loop per variant (the choice is made once per wave, outside the loop)
     auto k_loop = [&](auto tm_tag) {
-        int stage = 0;
-        for (int kt = 0; kt < KT; ++kt) {
+        int stage = 0, in_slice = 0;
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
             __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD & 15) | (((NS - 2) * NLOAD >> 4) << 14));   // vmcnt only
             __builtin_amdgcn_s_barrier();      // tile kt visible to all waves; all waves are done with tile kt-1
             asm volatile("" ::: "memory");
@@ -148,6 +177,14 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
             if (decltype(tm_tag)::value == 0) issue(min(kt + NS - 1, last), refill);
             else compute(tm_tag, smem + stage * STAGE_BYTES, min(kt + NS - 1, last), refill);
             stage = stage == NS - 1 ? 0 : stage + 1;
+            if (SL == 1 && decltype(tm_tag)::value != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
+        }
+        if (SL == 1 && decltype(tm_tag)::value != 0) {      // the last, possibly shorter slice; then the total goes to the epilogue
+            fold();
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = tot[SL == 1 ? i : 0][SL == 1 ? j : 0];
         }
     };
     if (vb == 0) k_loop(std::integral_constant<int, 0>{});
@@ -201,20 +238,52 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     }
 }
 
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3)>
-static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0>
+static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
+                       int slice_tiles = 0, int slices = 1) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
     static bool configured = false;
-    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD>;
+    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD, SL>;
     if (!configured) {      // dynamic LDS above the default limit has to be granted once per kernel
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n);
+    kern<<<dim3(grid, SL == 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles);
+}
+
+// Sum of the slice partials in ascending order, then the epilogue.  ws: [slices][MN] fp32; MN % 4 == 0.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4 *__restrict__ ws, int slices, size_t mn4, void *__restrict__ Cv) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= mn4) return;
+    float4 t = ws[i];
+    for (int s2 = 1; s2 < slices; ++s2) {
+        const float4 v = ws[(size_t)s2 * mn4 + i];
+        t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+    }
+    if (EPI == EPI_RESID_F32) {
+        float4 *c = reinterpret_cast<float4 *>(Cv) + i;
+        float4 o = *c;
+        o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+        *c = o;
+    } else if (EPI == EPI_F32_ROWMAJOR) {
+        reinterpret_cast<float4 *>(Cv)[i] = t;
+    } else {
+        bf16_t o[4] = {f2bf(t.x), f2bf(t.y), f2bf(t.z), f2bf(t.w)};
+        reinterpret_cast<uint2 *>(Cv)[i] = *reinterpret_cast<uint2 *>(o);
+    }
+}
+
+// K slices of a narrow GEMM: a function of K alone (never of M), so that every launch shape sums in the same order
+int gemm_slices(int K, int *slice_tiles) {
+    const int KT = K / 64;
+    const int want = KT >= 256 ? 8 : KT >= 48 ? 4 : KT >= 16 ? 2 : 1;
+    *slice_tiles = (KT + want - 1) / want;
+    return (KT + *slice_tiles - 1) / *slice_tiles;
 }
 
 template <int WGM, int WGN, int TM, int TN, int NS>
@@ -239,7 +308,8 @@ static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int 
 
 // A must be allocated for M rounded up to 256 rows, W for N rounded up to 256 rows; K % 64 == 0.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
-void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
+void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
+                 float *ws, size_t ws_floats) {
     if (M <= 0) return;
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
     //  * wide outputs (gate/up, LM head): 256x256, 8 waves (2 x 4) of 128x64 -- half the bytes per flop of a
@@ -249,10 +319,12 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     //  * few rows (T <= 512: weight streaming): 128x64 tiles, 5 stages, twice as many workgroups.
     // The SiLU epilogue pairs a gate block with the up block next to it, so its waves own two column blocks.
     if (M <= 320 && epi == EPI_SILU_FRAG && N >= 16384) {
-        // Few rows, wide gate/up: one M tile holds every row (each weight byte is fetched once) and 64-column tiles
-        // give ~600 workgroups; measured 13% faster than two 256x256 M tiles at T = 272.
-        if (M > 256) launch_one<5, 1, 2, 2, 3, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
-        else launch_one<4, 1, 2, 2, 3, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
+        // Few rows, wide gate/up (at the ridge between weight streaming and MFMA): 96x128 tiles (64x128 up to 64 rows),
+        // k-tiles of 32 in a five-stage ring, two workgroups per CU.  The M tiles of one weight tile run side by side on
+        // one XCD, so each weight byte leaves HBM once; per weight byte only 0.75 (0.5) bytes of activations come
+        // through the copy path.  Measured 10% faster at T = 272 than one 320x64 tile per weight tile.
+        if (M <= 64) launch_one<2, 2, 1, 2, 6, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
+        else launch_one<3, 2, 1, 2, 5, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
         return;
     }
     if (M > 256 && N >= 16384) {
@@ -268,9 +340,52 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
         return;
     }
-    else if (epi == EPI_SILU_FRAG) {
+    if (epi == EPI_SILU_FRAG) {
         if (M > 512) launch_one<4, 2, 1, 2, 4, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
         else launch_one<4, 1, 1, 2, 5, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
-    } else if (M > 512) launch_cfg3<2, 4, 2, 1, 4>(epi, A, W, C, M, N, K, ldc, st);
-    else launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
+        return;
+    }
+    if (N >= 16384) {      // wide output, up to 256 rows (LM head of a small batch): one pass over K like every wide GEMM
+        launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
+        return;
+    }
+    // Narrow outputs: K in slices (see gemm_kernel).  With few rows a 128x128 tile grid leaves most CUs idle and
+    // every workgroup walks all of K alone (down projection: 296 k-tiles), so the slices go to separate
+    // workgroups, 64-column tiles, two or more workgroups per CU, and a small kernel adds the partials in order.
+    int slice_tiles = 0;
+    const int slices = gemm_slices(K, &slice_tiles);
+    if (slices == 1) {
+        if (M > 512) launch_cfg3<2, 4, 2, 1, 4>(epi, A, W, C, M, N, K, ldc, st);
+        else launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
+        return;
+    }
+    const size_t mn = (size_t)M * N;
+    // few rows: slices over workgroups when the tile grid alone would not fill the chip or K is long
+    const bool few_tiles = M <= 64 || ((M + 127) / 128) * ((N + 63) / 64) < 200 || K >= 8192;
+    if (M <= 512 && few_tiles && ws && ldc == N && (N % 4) == 0 && ws_floats >= mn * slices) {
+        if (M <= 64) launch_one<1, 2, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 2>(A, W, ws, M, N, K, N, st, slice_tiles, slices);
+        else if (K >= 8192)      // long K (down projection): 128x128 tiles, k-tiles of 32 in an eight-stage ring (measured 13% faster)
+            launch_one<2, 4, 2, 1, 8, EPI_F32_ROWMAJOR, 2, true, 2>(A, W, ws, M, N, K, N, st, 2 * slice_tiles, slices);
+        else launch_one<2, 2, 2, 1, 3, EPI_F32_ROWMAJOR, 4, true, 2>(A, W, ws, M, N, K, N, st, slice_tiles, slices);
+        const size_t mn4 = mn / 4;
+        const dim3 g((unsigned)((mn4 + 255) / 256));
+        const float4 *w4 = reinterpret_cast<const float4 *>(ws);
+        if (epi == EPI_RESID_F32) gemm_reduce_kernel<EPI_RESID_F32><<<g, 256, 0, st>>>(w4, slices, mn4, C);
+        else if (epi == EPI_BF16_ROWMAJOR) gemm_reduce_kernel<EPI_BF16_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
+        else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
+        return;
+    }
+    if (M <= 512) {      // few rows, enough tiles (QKV at a few hundred rows): 128x64 tiles, slices folded in registers
+        switch (epi) {
+        case EPI_BF16_ROWMAJOR: launch_one<2, 2, 2, 1, 5, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        case EPI_RESID_F32: launch_one<2, 2, 2, 1, 5, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        default: launch_one<2, 2, 2, 1, 5, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        }
+        return;
+    }
+    switch (epi) {      // many rows: 128x128 tiles, one workgroup per tile folds the slices in registers
+    case EPI_BF16_ROWMAJOR: launch_one<2, 4, 2, 1, 4, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+    case EPI_RESID_F32: launch_one<2, 4, 2, 1, 4, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+    default: launch_one<2, 4, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+    }
 }

@@ -13,7 +13,8 @@ def das():
     return d
 
 
-@pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256), (520, 16512, 192), (257, 16384, 64), (560, 16640, 192)])
+@pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256), (520, 16512, 192), (257, 16384, 64), (560, 16640, 192),
+                                   (40, 320, 1024), (300, 256, 3584), (530, 192, 3136), (64, 128, 16448), (513, 96, 16384)])
 def test_mfma_gemm_against_fp64(das, M, N, K):
     rng = np.random.default_rng(M * 7 + N)
     a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
@@ -23,6 +24,21 @@ def test_mfma_gemm_against_fp64(das, M, N, K):
     ref = di.bf16_to_f32(a).astype(np.float64) @ di.bf16_to_f32(w).astype(np.float64).T
     # fp32 accumulation of exact bf16 products: error ~ sqrt(K) * eps_fp32 * |terms|
     np.testing.assert_allclose(c, ref, rtol=0, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("N,K", [(320, 3584), (192, 18944), (16416, 1024), (256, 960)])
+def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K):
+    """A row of the product is the same bits whether it is computed among 7, 70, 300 or 600 rows: narrow outputs sum
+    K in slices whose layout depends on K alone, whichever kernel shape (slices over workgroups, or folded in
+    registers) the row count selects; wide outputs sum K in one pass at every row count."""
+    rng = np.random.default_rng(N + K)
+    a = di.f32_to_bf16(rng.standard_normal((600, K)).astype(np.float32))
+    w = di.f32_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
+    full = das.debug_gemm(a, w)
+    for m in (7, 70, 300, 520):
+        print(f"gemm rows {m} of 600, N={N} K={K}", flush=True)
+        part = das.debug_gemm(a[:m], w)
+        assert np.array_equal(part, full[:m]), (m, float(np.abs(part - full[:m]).max()))
 
 
 def _small_model(das, shape, **kw):
