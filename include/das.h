@@ -133,7 +133,12 @@ int das_kv_synth(das_model *m, int32_t seq_id, uint64_t seed, uint64_t seq_key);
 /* ---- inspection (tests, parity harness, bench) ---- */
 /* Row count of the last forward pass that produced logits. */
 int das_debug_num_rows(das_model *m, int32_t *n_rows);
-/* fp32 logits of rows [first_row, first_row+n_rows) of the last pass; out[n_rows][vocab]. */
+/* Greedy passes do not write their logits to memory by default (vocab >= 16384): the LM-head GEMM gathers each
+ * row's argmax itself.  on != 0 makes every later pass write them, for das_debug_logits.  Passes with sampling
+ * always write them. */
+int das_debug_keep_logits(das_model *m, int32_t on);
+/* fp32 logits of rows [first_row, first_row+n_rows) of the last pass; out[n_rows][vocab].
+ * DAS_ERR_STATE if the last pass did not write them (see das_debug_keep_logits). */
 int das_debug_logits(das_model *m, int32_t first_row, int32_t n_rows, float *out);
 /* Greedy token of every row of the last pass; out[n_rows_of_pass]. */
 int das_debug_row_argmax(das_model *m, int32_t *out);

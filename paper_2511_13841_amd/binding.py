@@ -55,6 +55,7 @@ def lib():
             "das_kv_export": [P, I, I, I, I, VP, VP],
             "das_kv_synth": [P, I, C.c_uint64, C.c_uint64],
             "das_debug_num_rows": [P, C.POINTER(I)],
+            "das_debug_keep_logits": [P, I],
             "das_debug_logits": [P, I, I, VP],
             "das_debug_row_argmax": [P, VP],
             "das_debug_seq": [P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I), VP, C.POINTER(I)],
@@ -123,7 +124,7 @@ def debug_copy(nbytes, repeats=1):
 class DasModel:
     """Owner of one das_model handle.  Methods carry the C names without the das_ prefix."""
 
-    def __init__(self, cfg, weights_bf16, stream=None):
+    def __init__(self, cfg, weights_bf16, stream=None, keep_logits=False):
         self.cfg = cfg
         w = np.ascontiguousarray(weights_bf16, dtype=np.uint16)
         h = C.c_void_p()
@@ -136,6 +137,8 @@ class DasModel:
                 stream = None
         _chk(lib().das_model_load(C.byref(cfg), w.ctypes.data, C.c_void_p(stream or 0), C.byref(h)), "das_model_load")
         self.h = h
+        if keep_logits:
+            self.keep_logits(True)
 
     def free(self):
         if getattr(self, "h", None):
@@ -214,6 +217,11 @@ class DasModel:
 
     def kv_synth(self, seq_id, seed, seq_key):
         _chk(lib().das_kv_synth(self.h, int(seq_id), int(seed), int(seq_key)), "das_kv_synth")
+
+    def keep_logits(self, on=True):
+        """Make every later greedy pass write its fp32 logits (for debug_logits); by default the LM-head GEMM
+        gathers the row argmax itself and the logits are never stored."""
+        _chk(lib().das_debug_keep_logits(self.h, 1 if on else 0), "das_debug_keep_logits")
 
     def debug_num_rows(self):
         n = C.c_int32()

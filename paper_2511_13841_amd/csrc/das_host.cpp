@@ -74,6 +74,9 @@ struct das_model {
     std::vector<int> free_pages;
     std::vector<int> pending_upd;           // (index, page) pairs for the device page table
     int last_rows = 0;
+    bool keep_logits = false;        // materialise fp32 logits of every greedy pass (inspection); sampling always does
+    bool last_has_logits = false;
+    unsigned long long *d_keys = nullptr;   // (row maximum, ~column) keys gathered by the LM-head GEMM
     // profiling
     bool prof = false;
     struct Ev { int cls; hipEvent_t a, b; };
@@ -271,8 +274,19 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     }
     if (n_sel > 0) {
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, m->gf, m->xsel, pm.sel, n_sel, dm.d, dm.rms_eps, st); }
-        { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
-        { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
+        // Greedy passes need one number per row, the first column of the row maximum: the LM-head GEMM gathers it in
+        // its epilogue and the [rows][vocab] logits never reach memory.  Sampling, inspection mode and small
+        // vocabularies (narrow GEMM shapes) write the logits and scan them.
+        const bool fused = !m->keep_logits && !u_accept && !u_sample && dm.V >= 16384;
+        if (fused) {
+            { ProfScope ps(m, KC_ARGMAX); launch_rowmax_keys_clear(m->d_keys, n_sel, st); }
+            { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_ROWMAX, m->xsel, m->wlm, m->d_keys, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
+            { ProfScope ps(m, KC_ARGMAX); launch_rowmax_keys_decode(m->d_keys, n_sel, m->d_g, st); }
+        } else {
+            { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
+            { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
+        }
+        m->last_has_logits = !fused;
     }
     hipError_t le = hipGetLastError();
     if (le != hipSuccess) { g_dev_err = std::string("kernel launch: ") + hipGetErrorString(le); return DAS_ERR_DEVICE; }
@@ -380,7 +394,7 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     // ---- workspaces (row counts padded to 256 so GEMM tiles may over-read)
     A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->q_hi, Mp * qd); A(m->q_lo, Mp * qd); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
     A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
-    A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs);
+    A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs); A(m->d_keys, (size_t)c.max_rows);
     {   // slice partials of the narrow GEMMs when a pass has at most 512 rows: [slices <= 8][rows][widest narrow output]
         const size_t n_narrow = std::max<size_t>(std::max<size_t>(dm.qkvN, d), V < 16384 ? V : 0);
         m->gemm_ws_floats = 8 * std::min<size_t>(512, Mp) * n_narrow;
@@ -798,8 +812,14 @@ extern "C" int das_debug_num_rows(das_model *m, int32_t *n_rows) {
 extern "C" int das_debug_logits(das_model *m, int32_t first_row, int32_t n_rows, float *out) {
     if (!m || !out || first_row < 0 || n_rows < 0 || first_row + n_rows > m->last_rows) return DAS_ERR_INVALID;
     if (n_rows == 0) return DAS_OK;
+    if (!m->last_has_logits) return DAS_ERR_STATE;      // the last pass gathered its row maxima inside the GEMM
     HIPCHK(hipStreamSynchronize(m->st));
     HIPCHK(hipMemcpy(out, m->logits + (size_t)first_row * m->dm.V, (size_t)n_rows * m->dm.V * sizeof(float), hipMemcpyDeviceToHost));
+    return DAS_OK;
+}
+extern "C" int das_debug_keep_logits(das_model *m, int32_t on) {
+    if (!m) return DAS_ERR_INVALID;
+    m->keep_logits = on != 0;
     return DAS_OK;
 }
 extern "C" int das_debug_row_argmax(das_model *m, int32_t *out) {

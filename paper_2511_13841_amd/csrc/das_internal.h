@@ -74,7 +74,9 @@ struct PassMeta {
     int num_pages;         // pages in the pool
 };
 
-enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3 };
+// EPI_ROWMAX: no matrix is written; every row's (largest value, lowest column holding it) is folded into a 64-bit key per
+// row with atomic max (value in the high word as an order-preserving integer, ~column in the low word)
+enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3, EPI_ROWMAX = 4 };
 
 // ---- launchers (each enqueues on `st`; none synchronises) ----
 void launch_pack_weight(const bf16_t *src, bf16_t *dst, int N, int K, int Np, int Kp, hipStream_t st);
@@ -100,6 +102,8 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
 void launch_attn_merge(const PassMeta &pm, const uint16_t *part_o, const float *part_ml, bf16_t *out_frag,
                        const DasDims &dm, hipStream_t st);
 void launch_argmax(const float *logits, int n_rows, int V, int *out, hipStream_t st);
+void launch_rowmax_keys_clear(unsigned long long *keys, int n_rows, hipStream_t st);
+void launch_rowmax_keys_decode(const unsigned long long *keys, int n_rows, int *out, hipStream_t st);
 void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const int *tok, int NB,
                           int *accept_len, int *next_token, hipStream_t st);
 void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, float *stats, hipStream_t st);

@@ -133,7 +133,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
             for (int i = 0; i < TMV; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    if (EPI == EPI_SILU_FRAG)   // transposed block: rows = weight rows, cols = activation rows
+                    if (EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX)   // transposed block: rows = weight rows, cols = activation rows
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
                     else
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
@@ -218,6 +218,31 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                 }
             }
         }
+    } else if (EPI == EPI_ROWMAX) {
+        // transposed blocks: a lane holds 16 output columns of ONE row per block, in ascending column order, so the
+        // first strict maximum it meets is the lowest column of its share; lanes, waves and workgroups then meet in
+        // an atomic max over (value, ~column), whose result does not depend on the order of arrival
+        unsigned long long *keys = reinterpret_cast<unsigned long long *>(Cv);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + i * 32 + lr;
+            float best = -INFINITY;
+            int bi = 0x7FFFFFFF;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int col = n0 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    const float v = acc[i][j][r] + 0.f;      // -0 -> +0: equal values must give equal keys
+                    if (col < N && v > best) { best = v; bi = col; }
+                }
+            uint32_t u = __float_as_uint(best);
+            u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+            unsigned long long key = ((unsigned long long)u << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)bi);
+            const unsigned long long other = ((unsigned long long)__shfl_xor((int)(key >> 32), 32) << 32) | (uint32_t)__shfl_xor((int)(key & 0xFFFFFFFFu), 32);
+            if (other > key) key = other;
+            if (lh == 0 && row < M) atomicMax(keys + row, key);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -292,14 +317,16 @@ static void launch_cfg(int epi, const bf16_t *A, const bf16_t *W, void *C, int M
     case EPI_BF16_ROWMAJOR: launch_one<WGM, WGN, TM, TN, NS, EPI_BF16_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
     case EPI_RESID_F32: launch_one<WGM, WGN, TM, TN, NS, EPI_RESID_F32>(A, W, C, M, N, K, ldc, st); break;
     case EPI_SILU_FRAG: launch_one<WGM, WGN, TM, TN, NS, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st); break;
+    case EPI_ROWMAX: launch_one<WGM, WGN, TM, TN, NS, EPI_ROWMAX>(A, W, C, M, N, K, ldc, st); break;
     default: launch_one<WGM, WGN, TM, TN, NS, EPI_F32_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
     }
 }
 
-// the three epilogues that any wave layout supports
+// the epilogues that any wave layout supports
 template <int WGM, int WGN, int TM, int TN, int NS>
 static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st) {
     switch (epi) {
+    case EPI_ROWMAX: launch_one<WGM, WGN, TM, TN, NS, EPI_ROWMAX>(A, W, C, M, N, K, ldc, st); break;
     case EPI_BF16_ROWMAJOR: launch_one<WGM, WGN, TM, TN, NS, EPI_BF16_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
     case EPI_RESID_F32: launch_one<WGM, WGN, TM, TN, NS, EPI_RESID_F32>(A, W, C, M, N, K, ldc, st); break;
     default: launch_one<WGM, WGN, TM, TN, NS, EPI_F32_ROWMAJOR>(A, W, C, M, N, K, ldc, st); break;
@@ -307,6 +334,7 @@ static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int 
 }
 
 // A must be allocated for M rounded up to 256 rows, W for N rounded up to 256 rows; K % 64 == 0.
+// EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
                  float *ws, size_t ws_floats) {
@@ -333,6 +361,8 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
         else if (M <= 512 && epi == EPI_F32_ROWMAJOR)      // few rows (LM head at T ~ 300): spread the copies over the k-steps
             launch_one<2, 4, 4, 2, 2, EPI_F32_ROWMAJOR, 4, true>(A, W, C, M, N, K, ldc, st);
+        else if (M <= 512 && epi == EPI_ROWMAX)
+            launch_one<2, 4, 4, 2, 2, EPI_ROWMAX, 4, true>(A, W, C, M, N, K, ldc, st);
         else if (epi == EPI_SILU_FRAG)
             // gate/up at many rows: k-tiles of 32 in a four-stage ring, copies issued in slices between the k-steps
             // (same LDS, three tiles in flight instead of one; measured 4% faster than two stages of 64)

@@ -174,3 +174,21 @@ void launch_sample(const float *logits, int V, const int *tok, const int *b_row0
 void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, float *stats, hipStream_t st) {
     if (n_rows > 0) row_stats_kernel<<<dim3(n_rows), dim3(1024), 0, st>>>(logits, V, inv_temp, stats);
 }
+
+// ---------------------------------------------------------------- row maxima gathered by the LM-head GEMM itself
+// key = (order-preserving integer image of the value) << 32 | ~column: the largest key is the largest value at its
+// lowest column.  Keys start at zero (below the image of every float).
+__global__ void rowmax_keys_clear_kernel(unsigned long long *keys, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) keys[i] = 0ull;
+}
+__global__ void rowmax_keys_decode_kernel(const unsigned long long *keys, int n, int *out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (int)(0xFFFFFFFFu - (uint32_t)(keys[i] & 0xFFFFFFFFull));
+}
+void launch_rowmax_keys_clear(unsigned long long *keys, int n_rows, hipStream_t st) {
+    if (n_rows > 0) rowmax_keys_clear_kernel<<<(n_rows + 255) / 256, 256, 0, st>>>(keys, n_rows);
+}
+void launch_rowmax_keys_decode(const unsigned long long *keys, int n_rows, int *out, hipStream_t st) {
+    if (n_rows > 0) rowmax_keys_decode_kernel<<<(n_rows + 255) / 256, 256, 0, st>>>(keys, n_rows, out);
+}

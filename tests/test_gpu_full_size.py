@@ -89,6 +89,15 @@ def test_full_size_step_against_oracle_on_sampled_sequences(name, weights):
     print("verify step on the full batch", flush=True)
     acc, nx = dm.verify_step(ids, ctx, drafts, sampling)
     gg = dm.debug_row_argmax()
+    if sampling is None:
+        # that was the production path: row maxima gathered inside the LM-head GEMM, no logits in memory.  The same
+        # step with the logits written out and scanned must take the same decisions, bit for bit.
+        with pytest.raises(das.DasError):
+            dm.debug_logits(0, 1)
+        dm.kv_rollback(ids)
+        dm.keep_logits(True)
+        acc2, nx2 = dm.verify_step(ids, ctx, drafts, sampling)
+        assert np.array_equal(gg, dm.debug_row_argmax()) and np.array_equal(acc, acc2) and np.array_equal(nx, nx2)
     rep = StepReport()
     exact = 0
     for i in picks:

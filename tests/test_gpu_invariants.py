@@ -14,7 +14,7 @@ def _model(shape, B, max_ctx, pages, max_rows=512, max_draft=16):
     import paper_2511_13841_amd as das
     blob = di.weights_bf16(shape, seed=0)
     return das, das.DasModel(das.config_for(shape, max_seqs=B, max_ctx=max_ctx, max_rows=max_rows, max_draft=max_draft,
-                                            num_pages=pages), blob)
+                                            num_pages=pages), blob, keep_logits=True)
 
 
 @pytest.mark.parametrize("shape,ctxs", [(di.MODELS["tiny"], [17, 40, 64, 33]), (NARROW_7B, [100, 1020, 2500, 5000])],

@@ -28,7 +28,7 @@ def _setup(shape, ctxs, seed, max_draft=16, max_rows=512, weight_seed=0, sigma=0
     om = oracle.OracleModel(shape, di.bf16_to_f32(blob))
     pages = int(sum(-(-(c + 80) // 16) for c in ctxs)) + 8
     dm = das.DasModel(das.config_for(shape, max_seqs=len(ctxs), max_ctx=max(ctxs) + 128, max_rows=max_rows,
-                                     max_draft=max_draft, num_pages=pages), blob)
+                                     max_draft=max_draft, num_pages=pages), blob, keep_logits=True)
     mirror = oracle.PageTableMirror(pages)
     rng = np.random.default_rng(seed)
     ids = list(range(100, 100 + len(ctxs)))
@@ -113,7 +113,7 @@ def test_full_7b_widths_two_layers():
     om = oracle.OracleModel(shape, di.bf16_to_f32(blob))
     lens = [37, 150, 64]
     pages = 64
-    dm = das.DasModel(das.config_for(shape, max_seqs=4, max_ctx=512, max_rows=320, max_draft=16, num_pages=pages), blob)
+    dm = das.DasModel(das.config_for(shape, max_seqs=4, max_ctx=512, max_rows=320, max_draft=16, num_pages=pages), blob, keep_logits=True)
     mirror = oracle.PageTableMirror(pages)
     prompts = di.prompts(lens, shape.vocab, 77)
     ids = [1, 2, 3]

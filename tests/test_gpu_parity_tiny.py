@@ -18,7 +18,7 @@ def test_config1_end_to_end():
     blob = di.weights_bf16(shape, seed=0)
     om = oracle.OracleModel(shape, di.bf16_to_f32(blob))
     num_pages = 256
-    dm = das.DasModel(das.config_for(shape, max_seqs=8, max_ctx=1024, max_rows=256, max_draft=8, num_pages=num_pages), blob)
+    dm = das.DasModel(das.config_for(shape, max_seqs=8, max_ctx=1024, max_rows=256, max_draft=8, num_pages=num_pages), blob, keep_logits=True)
     mirror = oracle.PageTableMirror(num_pages)
     rng = np.random.default_rng(wl.seed)
     lens = di.context_lengths(wl)

@@ -24,7 +24,7 @@ def test_rejection_sampling_decisions_match_oracle(mode, tau):
     shape = di.MODELS["tiny"]
     blob = di.weights_bf16(shape, seed=0, sigma=0.06)          # sharper logits than config 1: p_max ~ 0.05
     om = oracle.OracleModel(shape, di.bf16_to_f32(blob))
-    dm = das.DasModel(das.config_for(shape, max_seqs=8, max_ctx=1024, max_rows=256, max_draft=8, num_pages=256), blob)
+    dm = das.DasModel(das.config_for(shape, max_seqs=8, max_ctx=1024, max_rows=256, max_draft=8, num_pages=256), blob, keep_logits=True)
     lens = [20, 33, 47, 64, 16]
     ids = list(range(5))
     prompts = di.prompts(lens, shape.vocab, 55)
