@@ -31,6 +31,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+import paper_2511_13841_amd as das                      # noqa: E402
 from paper_2511_13841_amd.rollout import Rollout      # noqa: E402
 
 
@@ -188,7 +189,7 @@ def main():
                 "share_of_step": e["ms_per_step"] / sum(v["ms_per_step"] for v in kernels.values())}
 
     if args.calibrate_copy:
-        ro.das.debug_copy(args.calibrate_copy << 20, 3)
+        das.debug_copy(args.calibrate_copy << 20, 3)
 
     cpu = None
     if not args.no_cpu_baseline and args.drafts == "trajectory" and wl.mode == "greedy":

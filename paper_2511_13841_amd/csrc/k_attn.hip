@@ -16,6 +16,7 @@
 //     verification and one-token decoding give bit-identical rows).
 // Wave w (of 8) owns query-row blocks (16 rows each) w*RBW .. w*RBW+RBW-1.
 #include "das_internal.h"
+#include <cstdlib>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -43,7 +44,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // Two waves per SIMD are asked for whenever the row blocks fit 256 registers: besides the occupancy, it
 // makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
 // without copies out of the accumulation register file on every tile.
-template <int D, int RBW, int NS, int MINW, int NW>
+template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const bf16_t *__restrict__ q_hi,
                                                            const bf16_t *__restrict__ q_lo,
@@ -150,8 +151,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             for (int i = 0; i < RBW; ++i) {
                 s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s.v[i][0], 0, 0, 0);
                 s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s.v[i][1], 0, 0, 0);
+                if (DBG != 2 && DBG != 4) {
                 s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[i][ks], s.v[i][0], 0, 0, 0);
                 s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[i][ks], s.v[i][1], 0, 0, 0);
+                }
             }
         }
     };
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
 #pragma unroll
             for (int i = 0; i < RBW; ++i) {
                 acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.hi[i], acc[i][db], 0, 0, 0);
-                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.lo[i], acc[i][db], 0, 0, 0);
+                if (DBG != 3 && DBG != 4) acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.lo[i], acc[i][db], 0, 0, 0);
             }
         }
     };
@@ -259,13 +262,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     issue(0, 0);
     if (ntiles > 1) issue(1, 1);
     int stage = 0;
+    const bool work = any_active && DBG != 1 && DBG != 7;
     for (int ti = 0; ti < ntiles; ti += 2) {
         __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0)
         __builtin_amdgcn_s_barrier();          // bare barrier: no fence needed, LDS is written by the copies only
         asm volatile("" ::: "memory");
-        if (ti + 2 < ntiles) issue(ti + 2, stage ^ 2);
-        if (ti + 3 < ntiles) issue(ti + 3, (stage ^ 2) + 1);
-        if (any_active) {
+        if (DBG != 6 && ti + 2 < ntiles) issue(ti + 2, stage ^ 2);
+        if (DBG != 6 && ti + 3 < ntiles) issue(ti + 3, (stage ^ 2) + 1);
+        if (work) {
             const unsigned char *c0 = smem + stage * TILE_B, *c1 = smem + (stage + 1) * TILE_B;
             Scores s0;
             Probs p0;
@@ -296,7 +300,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         const int rb = wave * RBW + i;
-        if (rb < nrb) {
+        if (rb < nrb && DBG != 7) {
             const size_t id = ((size_t)pm.b_prow[b] + (size_t)chunk * nrb + rb) * Hkv + kvh;
             if ((lane >> 4) == 0) *reinterpret_cast<float2 *>(part_ml + id * 32 + 2 * lane) = make_float2(m_run[i], l);
             const float inv = l > 0.f ? 1.f / l : 0.f;
@@ -319,6 +323,20 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     const size_t lds = 0;     // tile stages are static LDS arrays
     // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
     // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
+    const int dbg = getenv("DAS_ATTN_DBG") ? atoi(getenv("DAS_ATTN_DBG")) : 0;
+#define ATTN_LAUNCHD(DD, RB, DG) \
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    if (dbg && dm.D == 128) {
+        switch (dbg * 10 + (rbw <= 2 ? 1 : 2)) {
+        case 11: ATTN_LAUNCHD(128, 1, 1); return; case 12: ATTN_LAUNCHD(128, 2, 1); return;
+        case 21: ATTN_LAUNCHD(128, 1, 2); return; case 22: ATTN_LAUNCHD(128, 2, 2); return;
+        case 31: ATTN_LAUNCHD(128, 1, 3); return; case 32: ATTN_LAUNCHD(128, 2, 3); return;
+        case 41: ATTN_LAUNCHD(128, 1, 4); return; case 42: ATTN_LAUNCHD(128, 2, 4); return;
+        case 51: ATTN_LAUNCHD(128, 1, 5); return; case 52: ATTN_LAUNCHD(128, 2, 5); return;
+        case 61: ATTN_LAUNCHD(128, 1, 6); return; case 62: ATTN_LAUNCHD(128, 2, 6); return;
+        case 71: ATTN_LAUNCHD(128, 1, 7); return; case 72: ATTN_LAUNCHD(128, 2, 7); return;
+        }
+    }
 #define ATTN_LAUNCH(DD, RB) \
     attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
