@@ -44,6 +44,8 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // Two waves per SIMD are asked for whenever the row blocks fit 256 registers: besides the occupancy, it
 // makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
 // without copies out of the accumulation register file on every tile.
+// DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 2 / 3 / 4 without the lo term of
+// q / of p / of both, 6 arithmetic only (no copies after the first two tiles), 7 copies only and no partial stores.
 template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const bf16_t *__restrict__ q_hi,
@@ -323,6 +325,9 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     const size_t lds = 0;     // tile stages are static LDS arrays
     // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
     // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
+#ifdef DAS_ATTN_DEV
+    // Development build only (-DDAS_ATTN_DEV): variants that leave parts of the kernel out, to time copies and
+    // arithmetic separately.  Their results are wrong by design.  Selected by the DAS_ATTN_DBG environment variable.
     const int dbg = getenv("DAS_ATTN_DBG") ? atoi(getenv("DAS_ATTN_DBG")) : 0;
 #define ATTN_LAUNCHD(DD, RB, DG) \
     attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
@@ -332,11 +337,12 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
         case 21: ATTN_LAUNCHD(128, 1, 2); return; case 22: ATTN_LAUNCHD(128, 2, 2); return;
         case 31: ATTN_LAUNCHD(128, 1, 3); return; case 32: ATTN_LAUNCHD(128, 2, 3); return;
         case 41: ATTN_LAUNCHD(128, 1, 4); return; case 42: ATTN_LAUNCHD(128, 2, 4); return;
-        case 51: ATTN_LAUNCHD(128, 1, 5); return; case 52: ATTN_LAUNCHD(128, 2, 5); return;
         case 61: ATTN_LAUNCHD(128, 1, 6); return; case 62: ATTN_LAUNCHD(128, 2, 6); return;
         case 71: ATTN_LAUNCHD(128, 1, 7); return; case 72: ATTN_LAUNCHD(128, 2, 7); return;
         }
     }
+#undef ATTN_LAUNCHD
+#endif
 #define ATTN_LAUNCH(DD, RB) \
     attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
