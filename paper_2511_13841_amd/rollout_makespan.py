@@ -104,15 +104,28 @@ def decode_speculative(dm, ids, ctx0, lens, traj, budgets, p, vocab, seed):
     return out, time.perf_counter() - t0, rounds, n_toks, accepted
 
 
+def solver_budgets(lens, c_base, c_tok, alpha, cap, k_max):
+    """Per-sequence chain lengths from the budget model of Sec. 4.2.1 (das_budget_solve): target lengths as l_i, one
+    accept efficiency and capacity factor for the whole batch, the forward-latency constants of Eq. 1."""
+    from . import budget
+    reqs = [(float(l), alpha, cap) for l in lens]
+    n_fwd, p = budget.solve(reqs, c_base, c_tok)
+    return budget.draft_lens(p, n_fwd, k_max).astype(np.int64), n_fwd
+
+
 def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, ctx_lo=256, ctx_hi=1024, seed=4000,
-        n_layers=None):
+        n_layers=None, policy="classes", c_base=8.0, c_tok=0.017, alpha=0.6, cap=0.9):
     shape = di.MODELS[model]
     if n_layers is not None:
         shape = shape.replace(n_layers=n_layers)
     rng = np.random.default_rng(seed)
     ctx0 = rng.integers(ctx_lo, ctx_hi + 1, size=batch).astype(np.int64)
     lens = target_lengths(batch, max_len, seed + 1)
-    budgets = class_budgets(lens, k_medium, k_long)
+    predicted_n_fwd = None
+    if policy == "solver":
+        budgets, predicted_n_fwd = solver_budgets(lens, c_base, c_tok, alpha, cap, max(k_medium, k_long, 1))
+    else:
+        budgets = class_budgets(lens, k_medium, k_long)
     kmax = int(max(k_medium, k_long, 1))
     room = int(max_len) + kmax + 4
     pages = int(sum(-(-(int(c) + room) // 16) for c in ctx0)) + 16
@@ -136,7 +149,9 @@ def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, c
     dm.free()
     half = next((r for r, n in enumerate(hist) if n <= batch // 2), len(hist))
     return {"model": model, "n_layers": shape.n_layers, "batch": batch, "accept_p": accept_p,
-            "budgets": {"short": 0, "medium": k_medium, "long": k_long},
+            "policy": policy, "budgets": {"short": 0, "medium": k_medium, "long": k_long} if policy == "classes" else
+            {"k_max": kmax, "mean_k": float(np.mean(budgets)), "sequences_without_speculation": int((budgets == 0).sum()),
+             "model_forward_passes": predicted_n_fwd},
             "target_len": {"median": int(np.median(lens)), "max": int(lens.max()), "sum": int(lens.sum())},
             "plain": {"makespan_s": t_plain, "forwards": r_plain, "tokens_processed": n_plain,
                       "forwards_until_half_the_batch_is_done": half},
@@ -155,8 +170,15 @@ def main():
     ap.add_argument("--k-medium", type=int, default=4)
     ap.add_argument("--k-long", type=int, default=8)
     ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--policy", choices=["classes", "solver"], default="classes",
+                    help="classes: none/medium/long chains by target-length third; solver: chain lengths from das_budget_solve")
+    ap.add_argument("--c-base", type=float, default=8.0, help="ms per forward pass (Eq. 1), for --policy solver")
+    ap.add_argument("--c-tok", type=float, default=0.017, help="ms per processed token (Eq. 1), for --policy solver")
+    ap.add_argument("--alpha", type=float, default=0.6, help="accept efficiency of the drafter (Eq. 3), for --policy solver")
+    ap.add_argument("--cap", type=float, default=0.9, help="drafter capacity factor k (Eq. 3), for --policy solver")
     a = ap.parse_args()
-    print(json.dumps(run(a.model, a.batch, a.max_len, a.accept_p, a.k_medium, a.k_long, n_layers=a.layers)))
+    print(json.dumps(run(a.model, a.batch, a.max_len, a.accept_p, a.k_medium, a.k_long, n_layers=a.layers, policy=a.policy,
+                         c_base=a.c_base, c_tok=a.c_tok, alpha=a.alpha, cap=a.cap)))
 
 
 if __name__ == "__main__":

@@ -19,3 +19,12 @@ def test_speculative_rollout_equals_plain_rollout_wide_model_few_layers():
     r = run(model="1.5b", batch=6, max_len=24, accept_p=0.8, k_medium=3, k_long=6, ctx_lo=200, ctx_hi=2300, seed=78, n_layers=2)
     assert r["sequences_differing_from_plain_decoding"] == 0
     assert r["speculative"]["forwards"] < r["plain"]["forwards"]
+
+
+def test_rollout_with_solver_budgets_is_lossless_too():
+    from paper_2511_13841_amd.rollout_makespan import run
+    r = run(model="tiny", batch=12, max_len=48, accept_p=0.7, k_long=6, ctx_lo=16, ctx_hi=64, seed=79, policy="solver",
+            c_base=1.0, c_tok=0.02, alpha=0.6, cap=0.9)
+    assert r["sequences_differing_from_plain_decoding"] == 0
+    assert r["speculative"]["forwards"] < r["plain"]["forwards"]
+    assert r["budgets"]["sequences_without_speculation"] > 0        # short requests skip speculation (Sec. 4.2.1)
