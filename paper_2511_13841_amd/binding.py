@@ -39,6 +39,10 @@ def lib():
         if not os.path.exists(_SO):
             raise ImportError(f"{_SO} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                               "(hipcc --offload-arch=gfx950); there is no CPU fallback")
+        try:                # PyTorch ships its own HIP runtime: let it load first, so that this library binds to the same one
+            import torch    # noqa: F401  (loading the library first and torch afterwards leaves the process with two runtimes and no device)
+        except Exception:
+            pass
         L = C.CDLL(_SO)
         P, I, VP = C.c_void_p, C.c_int32, C.c_void_p
         sig = {

@@ -67,10 +67,10 @@ def decode_plain(dm, ids, ctx0, pend0, lens):
     return traj, time.perf_counter() - t0, rounds, n_toks, active_hist
 
 
-def decode_speculative(dm, ids, ctx0, lens, traj, budgets, p, vocab, seed):
+def decode_speculative(dm, ids, ctx0, lens, traj, budgets, p, vocab, seed, tree=None):
     B = len(ids)
     rng = np.random.default_rng(seed)
-    # the drafter's view of every sequence: its true continuation, each position kept with probability p
+    # synthetic drafter's view of every sequence: its true continuation, each position kept with probability p
     prop = []
     for i in range(B):
         t = traj[i].copy()
@@ -90,7 +90,10 @@ def decode_speculative(dm, ids, ctx0, lens, traj, budgets, p, vocab, seed):
         drafts = []
         for i in act:
             k = int(min(budgets[i], lens[i] - done[i] - 1))        # never draft past the target length
-            drafts.append(prop[i][done[i] + 1: done[i] + 1 + max(k, 0)])
+            if tree is not None:                                   # suffix-tree drafter: longest match of what was emitted so far
+                drafts.append(tree.propose(out[i][:done[i] + 1], max(k, 0))[1] if k > 0 else prop[i][:0])
+            else:
+                drafts.append(prop[i][done[i] + 1: done[i] + 1 + max(k, 0)])
         acc, nxt = dm.verify_step([ids[i] for i in act], [ctx0[i] + done[i] for i in act], drafts)
         dm.kv_commit([ids[i] for i in act], acc, nxt)
         for j, i in enumerate(act):
@@ -114,7 +117,7 @@ def solver_budgets(lens, c_base, c_tok, alpha, cap, k_max):
 
 
 def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, ctx_lo=256, ctx_hi=1024, seed=4000,
-        n_layers=None, policy="classes", c_base=8.0, c_tok=0.017, alpha=0.6, cap=0.9):
+        n_layers=None, policy="classes", c_base=8.0, c_tok=0.017, alpha=0.6, cap=0.9, drafter="synthetic"):
     shape = di.MODELS[model]
     if n_layers is not None:
         shape = shape.replace(n_layers=n_layers)
@@ -142,13 +145,24 @@ def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, c
     traj, t_plain, r_plain, n_plain, hist = decode_plain(dm, ids, ctx0, pend0, lens)
     log(f"[makespan] plain decoding: {t_plain:.3f}s, {r_plain} forwards, {n_plain} tokens")
     dm.seq_rewind(ids, ctx0, pend0)
+    tree = None
+    if drafter == "tree":
+        # the previous epoch's rollouts of the same prompts, indexed in a suffix tree (Sec. 4.1.2); the policy has not
+        # moved between the two epochs here, the limit of the recency effect the paper builds on
+        from .drafter import Drafter
+        tree = Drafter(max_epochs=1)
+        t0 = time.perf_counter()
+        for t in traj:
+            tree.add(t)
+        log(f"[makespan] suffix tree over {tree.size()['tokens']} tokens built in {(time.perf_counter() - t0) * 1e3:.1f} ms")
     out, t_spec, r_spec, n_spec, accepted = decode_speculative(dm, ids, ctx0, lens, traj, budgets, accept_p,
-                                                               shape.vocab, seed + 2)
+                                                               shape.vocab, seed + 2, tree)
     log(f"[makespan] speculative: {t_spec:.3f}s, {r_spec} forwards, {n_spec} tokens processed, {accepted} drafts accepted")
     mismatched = sum(int(not np.array_equal(out[i], traj[i])) for i in ids)
     dm.free()
     half = next((r for r, n in enumerate(hist) if n <= batch // 2), len(hist))
-    return {"model": model, "n_layers": shape.n_layers, "batch": batch, "accept_p": accept_p,
+    return {"model": model, "n_layers": shape.n_layers, "batch": batch, "drafter": drafter,
+            "accept_p": accept_p if drafter == "synthetic" else None,
             "policy": policy, "budgets": {"short": 0, "medium": k_medium, "long": k_long} if policy == "classes" else
             {"k_max": kmax, "mean_k": float(np.mean(budgets)), "sequences_without_speculation": int((budgets == 0).sum()),
              "model_forward_passes": predicted_n_fwd},
@@ -172,13 +186,15 @@ def main():
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--policy", choices=["classes", "solver"], default="classes",
                     help="classes: none/medium/long chains by target-length third; solver: chain lengths from das_budget_solve")
+    ap.add_argument("--drafter", choices=["synthetic", "tree"], default="synthetic",
+                    help="synthetic: the recorded continuation corrupted with probability 1-p; tree: das_drafter over the plain pass's rollouts")
     ap.add_argument("--c-base", type=float, default=8.0, help="ms per forward pass (Eq. 1), for --policy solver")
     ap.add_argument("--c-tok", type=float, default=0.017, help="ms per processed token (Eq. 1), for --policy solver")
     ap.add_argument("--alpha", type=float, default=0.6, help="accept efficiency of the drafter (Eq. 3), for --policy solver")
     ap.add_argument("--cap", type=float, default=0.9, help="drafter capacity factor k (Eq. 3), for --policy solver")
     a = ap.parse_args()
     print(json.dumps(run(a.model, a.batch, a.max_len, a.accept_p, a.k_medium, a.k_long, n_layers=a.layers, policy=a.policy,
-                         c_base=a.c_base, c_tok=a.c_tok, alpha=a.alpha, cap=a.cap)))
+                         c_base=a.c_base, c_tok=a.c_tok, alpha=a.alpha, cap=a.cap, drafter=a.drafter)))
 
 
 if __name__ == "__main__":

@@ -28,3 +28,12 @@ def test_rollout_with_solver_budgets_is_lossless_too():
     assert r["sequences_differing_from_plain_decoding"] == 0
     assert r["speculative"]["forwards"] < r["plain"]["forwards"]
     assert r["budgets"]["sequences_without_speculation"] > 0        # short requests skip speculation (Sec. 4.2.1)
+
+
+def test_rollout_with_the_suffix_tree_drafter_over_the_previous_epoch():
+    from paper_2511_13841_amd.rollout_makespan import run
+    r = run(model="tiny", batch=12, max_len=48, k_medium=3, k_long=6, ctx_lo=16, ctx_hi=64, seed=81, drafter="tree")
+    assert r["sequences_differing_from_plain_decoding"] == 0
+    # same policy in both epochs: once the match is unique the tree proposes the true continuation
+    assert r["speculative"]["accepted_drafts"] > 0.5 * (r["speculative"]["tokens_processed"] - r["speculative"]["forwards"])
+    assert r["speculative"]["forwards"] < 0.7 * r["plain"]["forwards"]
