@@ -137,6 +137,7 @@ def main():
     ap.add_argument("--faithful", action="store_true",
                     help="stochastic workload: honest accept uniforms everywhere (acceptance ~0 on random-init weights)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rollback", action="store_true", help="roll every step back instead of committing it (contexts stay fixed; also for development kernels whose outputs are not valid)")
     ap.add_argument("--no-profile", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -149,6 +150,7 @@ def main():
     K, W = args.steps, args.warmup
     ro = Rollout(wl, batch=args.batch, n_layers=args.layers, context=args.context, max_steps=W + 2 * K + 1)
     ro.faithful = args.faithful
+    ro.rollback = args.rollback
     if args.drafts == "trajectory" and wl.mode == "greedy":
         ro.generate_trajectories()
     else:

@@ -59,6 +59,7 @@ class Rollout:
         self.pending = self.pending0.copy()
         self.future = None
         self.faithful = False
+        self.rollback = False            # time the verify pass alone: every step is rolled back instead of committed
 
     def generate_trajectories(self):
         """Plain decoding (k=0 verify steps) for `horizon` tokens, then rewind.  future[i][0] is the pending token."""
@@ -105,6 +106,9 @@ class Rollout:
         if sampling is None and self.wl.mode == "stochastic":
             sampling = self.sampling_inputs(ks)
         acc, nxt = self.dm.verify_step(self.ids, self.ctx, drafts, sampling)
+        if self.rollback:
+            self.dm.kv_rollback(self.ids)
+            return ks, acc, nxt
         self.dm.kv_commit(self.ids, acc, nxt)
         self.ctx = self.ctx + 1 + acc
         self.emitted += 1 + acc
