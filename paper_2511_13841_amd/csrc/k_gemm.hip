@@ -413,7 +413,28 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         }
         return;
     }
-    switch (epi) {      // many rows: 128x128 tiles, one workgroup per tile folds the slices in registers
+    // Many rows: one workgroup per tile folds the slices in registers.  128x128 tiles (8 waves), or 192x128 (12 waves) when
+    // that needs fewer rounds of workgroups times tile height: 1560 rows x 3584 columns are 364 tiles of 128 rows (two
+    // rounds on 256 CUs) but 252 tiles of 192 rows (one round).
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        (void)hipGetLastError();
+        n_cu = cus;
+    }
+    const int tn = (N + 127) / 128;
+    const long cost128 = (long)((((M + 127) / 128) * tn + n_cu - 1) / n_cu) * 128;
+    const long cost192 = (long)((((M + 191) / 192) * tn + n_cu - 1) / n_cu) * 192;
+    if (cost192 < cost128) {
+        switch (epi) {
+        case EPI_BF16_ROWMAJOR: launch_one<3, 4, 2, 1, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        case EPI_RESID_F32: launch_one<3, 4, 2, 1, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        default: launch_one<3, 4, 2, 1, 3, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        }
+        return;
+    }
+    switch (epi) {
     case EPI_BF16_ROWMAJOR: launch_one<2, 4, 2, 1, 4, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
     case EPI_RESID_F32: launch_one<2, 4, 2, 1, 4, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
     default: launch_one<2, 4, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
