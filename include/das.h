@@ -140,7 +140,8 @@ int das_debug_keep_logits(das_model *m, int32_t on);
 /* fp32 logits of rows [first_row, first_row+n_rows) of the last pass; out[n_rows][vocab].
  * DAS_ERR_STATE if the last pass did not write them (see das_debug_keep_logits). */
 int das_debug_logits(das_model *m, int32_t first_row, int32_t n_rows, float *out);
-/* Greedy token of every row of the last pass; out[n_rows_of_pass]. */
+/* Greedy token of every row of the last pass; out[n_rows_of_pass].  DAS_ERR_STATE after a sampling pass unless
+ * das_debug_keep_logits is on (sampling does not need the argmax). */
 int das_debug_row_argmax(das_model *m, int32_t *out);
 /* Sequence state: committed length, pending token, state (0 COMMITTED, 1 SPECULATIVE), page list.
  * pages may be NULL; *n_pages receives the count (pages must hold that many when non-NULL). */

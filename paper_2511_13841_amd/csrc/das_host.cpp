@@ -75,7 +75,7 @@ struct das_model {
     std::vector<int> pending_upd;           // (index, page) pairs for the device page table
     int last_rows = 0;
     bool keep_logits = false;        // materialise fp32 logits of every greedy pass (inspection); sampling always does
-    bool last_has_logits = false;
+    bool last_has_logits = false, last_has_argmax = false;
     unsigned long long *d_keys = nullptr;   // (row maximum, ~column) keys gathered by the LM-head GEMM
     // profiling
     bool prof = false;
@@ -284,8 +284,11 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
             { ProfScope ps(m, KC_ARGMAX); launch_rowmax_keys_decode(m->d_keys, n_sel, m->d_g, st); }
         } else {
             { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
-            { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
+            // the row argmax is what greedy acceptance reads; a sampling pass needs it only for inspection
+            if (!(u_accept || u_sample) || m->keep_logits) { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
+            m->last_has_argmax = !(u_accept || u_sample) || m->keep_logits;
         }
+        if (fused) m->last_has_argmax = true;
         m->last_has_logits = !fused;
     }
     hipError_t le = hipGetLastError();
@@ -825,6 +828,7 @@ extern "C" int das_debug_keep_logits(das_model *m, int32_t on) {
 extern "C" int das_debug_row_argmax(das_model *m, int32_t *out) {
     if (!m || !out) return DAS_ERR_INVALID;
     if (m->last_rows == 0) return DAS_OK;
+    if (!m->last_has_argmax) return DAS_ERR_STATE;      // a sampling pass outside inspection mode does not compute it
     HIPCHK(hipStreamSynchronize(m->st));
     HIPCHK(hipMemcpy(out, m->d_g, (size_t)m->last_rows * sizeof(int), hipMemcpyDeviceToHost));
     return DAS_OK;

@@ -62,26 +62,38 @@ void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const
 // row_stats[r] = (max logit, Z = sum exp((l - max)/T))
 __global__ __launch_bounds__(1024) void row_stats_kernel(const float *__restrict__ logits, int V, float inv_temp,
                                                          float *__restrict__ stats) {
-    __shared__ float red[16];
+    // one pass over the row: every thread keeps a running (max, sum of exp relative to that max) over its elements and
+    // the pairs are then combined in a fixed order (lanes by butterfly, waves in index order)
+    __shared__ float red_m[16], red_z[16];
     const float *x = logits + (size_t)blockIdx.x * V;
-    float mx = -INFINITY;
-    for (int i = threadIdx.x; i < V; i += 1024) mx = fmaxf(mx, x[i]);
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
-    __syncthreads();
-    mx = red[0];
-    for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
-    __syncthreads();
-    float z = 0.f;
-    for (int i = threadIdx.x; i < V; i += 1024) z += __expf((x[i] - mx) * inv_temp);
-    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = z;
+    float mx = -INFINITY, z = 0.f;
+    auto add = [&](float v) {
+        if (v > mx) { z = z * __expf((mx - v) * inv_temp) + 1.f; mx = v; }      // exp(-inf) = 0 on the first element
+        else z += __expf((v - mx) * inv_temp);
+    };
+    const int nv4 = V >> 2;
+    for (int c = threadIdx.x; c < nv4; c += 1024) {
+        const float4 v = reinterpret_cast<const float4 *>(x)[c];
+        add(v.x); add(v.y); add(v.z); add(v.w);
+    }
+    for (int i = (nv4 << 2) + threadIdx.x; i < V; i += 1024) add(x[i]);
+    auto merge = [&](float om, float oz) {
+        const float nm = fmaxf(mx, om);
+        if (nm == -INFINITY) return;                                          // both empty
+        z = z * __expf((mx - nm) * inv_temp) + oz * __expf((om - nm) * inv_temp);
+        mx = nm;
+    };
+    for (int o = 32; o > 0; o >>= 1) {
+        const float om = __shfl_xor(mx, o), oz = __shfl_xor(z, o);
+        merge(om, oz);
+    }
+    if ((threadIdx.x & 63) == 0) { red_m[threadIdx.x >> 6] = mx; red_z[threadIdx.x >> 6] = z; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        float t = 0.f;
-        for (int w = 0; w < 16; ++w) t += red[w];
+        mx = red_m[0]; z = red_z[0];
+        for (int w = 1; w < 16; ++w) merge(red_m[w], red_z[w]);
         stats[2 * blockIdx.x] = mx;
-        stats[2 * blockIdx.x + 1] = t;
+        stats[2 * blockIdx.x + 1] = z;
     }
 }
 
