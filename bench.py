@@ -66,13 +66,22 @@ def kernel_rooflines(shape, prof, T, kv_tokens, n_steps):
     return out
 
 
+def _gemm_epilogue(kernel_name):
+    """Sixth template argument of gemm_kernel<...> (the epilogue), or None for other kernels."""
+    if not kernel_name.startswith("gemm_kernel<"):
+        return None
+    args = kernel_name[len("gemm_kernel<"):].rstrip(">").split(", ")
+    return args[5] if len(args) > 5 else None
+
+
 def stored_traffic(workload, kernel_class):
     """HBM-side bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
     scaled by the plain copy kernel), if one exists for this workload and kernel class; else None."""
     path = os.path.join(ROOT, "profiles", f"verify_step_{workload}_traffic.json")
     match = {"attention": lambda k: k.startswith("attn_partial_kernel"),
              "attention_merge": lambda k: k.startswith("attn_merge_kernel"),
-             "gemm_gateup_silu": lambda k: k.startswith("gemm_kernel") and k.endswith(", 2>")}.get(kernel_class)
+             "gemm_gateup_silu": lambda k: _gemm_epilogue(k) == "2",
+             "gemm_lm_head": lambda k: _gemm_epilogue(k) == "4"}.get(kernel_class)
     if not match or not os.path.exists(path):
         return None
     per = json.load(open(path))["per_launch"]

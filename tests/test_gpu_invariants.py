@@ -17,7 +17,7 @@ def _model(shape, B, max_ctx, pages, max_rows=512, max_draft=16):
                                             num_pages=pages), blob, keep_logits=True)
 
 
-@pytest.mark.parametrize("shape,ctxs", [(di.MODELS["tiny"], [17, 40, 64, 33]), (NARROW_7B, [100, 1020, 2500, 5000])],
+@pytest.mark.parametrize("shape,ctxs", [(di.MODELS["tiny"], [17, 40, 64, 33]), (NARROW_7B, [100, 1020, 2040, 5000])],
                          ids=["tiny", "7b-heads"])
 def test_gpu_speculative_rounds_equal_gpu_plain_decoding(shape, ctxs):
     """The emitted stream of speculative rounds (ragged budgets, a changing batch) is bit-identical to
@@ -137,6 +137,8 @@ def test_error_paths_leave_state_untouched():
         except E as e:
             return e.code
         return 0
+    acc0, nxt0 = dm.verify_step([], [], [])                                        # an empty batch is a no-op
+    assert len(acc0) == 0 and len(nxt0) == 0 and code(dm.kv_commit, [], [], []) == 0 and code(dm.kv_rollback, []) == 0
     assert code(dm.prefill, [3], [prompts[0]]) == das.DAS_ERR_NOMEM               # no slot
     assert code(dm.verify_step, [1, 2], [40, 31], [[1], [2]]) == das.DAS_ERR_STATE  # ctx mismatch
     assert code(dm.verify_step, [1, 1], [40, 40], [[1], [2]]) == das.DAS_ERR_INVALID
