@@ -36,7 +36,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // launches can spread the slices over workgroups without changing a single bit of the result:
 // 1: this workgroup walks all slices and folds each finished slice into a second set of registers;
 // 2: this workgroup computes slice blockIdx.y and stores the raw fp32 partial to slab blockIdx.y of Cv ([slices][M][ldc]).
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
                                                              int tiles_m, int tiles_n, int slice_tiles) {
@@ -187,9 +187,83 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                 for (int j = 0; j < TN; ++j) acc[i][j] = tot[SL == 1 ? i : 0][SL == 1 ? j : 0];
         }
     };
-    if (vb == 0) k_loop(std::integral_constant<int, 0>{});
-    else if (TM == 4 && vb <= 2) k_loop(std::integral_constant<int, (TM == 4 ? 2 : TM)>{});
-    else k_loop(std::integral_constant<int, TM>{});
+    // PIPE: the k loop pipelined across k-tiles.  The barrier that publishes tile kt+1 sits before the LAST k-step of tile
+    // kt, and the first fragments of tile kt+1 are requested right after it, so that their LDS latency (and the wait at
+    // the barrier of the slower waves) passes under the MFMAs of that last k-step instead of in front of an idle matrix
+    // pipe -- which is what a workgroup with one wave per SIMD cannot afford.  Needs NS >= 3 and spread copies: the
+    // copy of tile kt+NS-1 starts after that barrier (every wave has left tile kt-1) and its remaining slices follow
+    // in the first k-steps of tile kt+1; all of them are issued before the next such barrier, so "tile kt+1 has
+    // landed" is again one constant s_waitcnt: at most NS-3 newer tiles outstanding.
+    auto k_loop_pipe = [&](auto tm_tag) {
+        constexpr int TMV = decltype(tm_tag)::value;
+        static_assert(!PIPE || (NS >= 3 && SPREAD && KS % 2 == 0), "pipelined k loop: three stages, spread copies, even k-steps");
+        bf16x8 a[2][TMV > 0 ? TMV : 1], b[2][TN];
+        auto fetch = [&](const unsigned char *cur, int ks, int buf) {
+#pragma unroll
+            for (int i = 0; i < TMV; ++i)
+                a[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + i) * KS + ks) * 1024 + lane * 16);
+            if (TMV > 0) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    b[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((wn * TN + j) * KS + ks) * 1024 + lane * 16);
+            }
+        };
+        int stage = 0, in_slice = 0;
+        __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD & 15) | (((NS - 2) * NLOAD >> 4) << 14));
+        __builtin_amdgcn_s_barrier();          // the first tile is there
+        asm volatile("" ::: "memory");
+        fetch(smem, 0, 0);
+        int pend_kt = 0, pend_stage = 0;       // tile whose later copy slices are still to be issued
+        bool pending = false;
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            const unsigned char *cur = smem + stage * STAGE_BYTES;
+            const int next_stage = stage == NS - 1 ? 0 : stage + 1;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == KS - 1) {
+                    if (kt + 1 < kt_end) {
+                        constexpr int NEWER = NS >= 3 ? (NS - 3) * NLOAD : 0;
+                        __builtin_amdgcn_s_waitcnt(0xF70 | (NEWER & 15) | ((NEWER >> 4) << 14));
+                        __builtin_amdgcn_s_barrier();      // tile kt+1 visible to all waves; all waves have left tile kt-1
+                        asm volatile("" ::: "memory");
+                        fetch(smem + next_stage * STAGE_BYTES, 0, 0);
+                        pend_kt = min(kt + NS - 1, last); pend_stage = stage == 0 ? NS - 1 : stage - 1; pending = true;
+                        issue_slice(pend_kt, pend_stage, 0);
+                    } else pending = false;
+                } else {
+                    fetch(cur, ks + 1, (ks + 1) & 1);
+                    if (pending) issue_slice(pend_kt, pend_stage, ks + 1);
+                }
+#pragma unroll
+                for (int i = 0; i < TMV; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if (EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+                    }
+            }
+            stage = next_stage;
+            if (SL == 1 && TMV != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
+        }
+        if (SL == 1 && TMV != 0) {
+            fold();
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = tot[SL == 1 ? i : 0][SL == 1 ? j : 0];
+        }
+    };
+    if (PIPE) {
+        if (vb == 0) k_loop_pipe(std::integral_constant<int, 0>{});
+        else if (TM == 4 && vb <= 2) k_loop_pipe(std::integral_constant<int, (TM == 4 ? 2 : TM)>{});
+        else k_loop_pipe(std::integral_constant<int, TM>{});
+    } else {
+        if (vb == 0) k_loop(std::integral_constant<int, 0>{});
+        else if (TM == 4 && vb <= 2) k_loop(std::integral_constant<int, (TM == 4 ? 2 : TM)>{});
+        else k_loop(std::integral_constant<int, TM>{});
+    }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
     const int m0 = tile_m * AB * 32 + wm * TM * 32, n0 = tile_n * BB * 32 + wn * TN * 32;
@@ -263,14 +337,14 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     }
 }
 
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false>
 static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
                        int slice_tiles = 0, int slices = 1) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
     static bool configured = false;
-    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD, SL>;
+    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD, SL, PIPE>;
     if (!configured) {      // dynamic LDS above the default limit has to be granted once per kernel
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
@@ -365,8 +439,9 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             launch_one<2, 4, 4, 2, 2, EPI_ROWMAX, 4, true>(A, W, C, M, N, K, ldc, st);
         else if (epi == EPI_SILU_FRAG)
             // gate/up at many rows: k-tiles of 32 in a four-stage ring, copies issued in slices between the k-steps
-            // (same LDS, three tiles in flight instead of one; measured 4% faster than two stages of 64)
-            launch_one<2, 4, 4, 2, 4, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
+            // (same LDS, three tiles in flight instead of one; measured 4% faster than two stages of 64), k loop pipelined
+            // across k-tiles (another 3%; no gain for the narrow shapes or for one wave per SIMD with 128x128 per wave)
+            launch_one<2, 4, 4, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
         return;
     }
