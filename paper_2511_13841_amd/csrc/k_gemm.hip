@@ -197,43 +197,56 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     auto k_loop_pipe = [&](auto tm_tag) {
         constexpr int TMV = decltype(tm_tag)::value;
         static_assert(!PIPE || (NS >= 3 && SPREAD && KS % 2 == 0), "pipelined k loop: three stages, spread copies, even k-steps");
+        constexpr int NMF = TMV * TN, NRD = TMV > 0 ? TMV + TN : 0;      // MFMAs and fragment reads per k-step
         bf16x8 a[2][TMV > 0 ? TMV : 1], b[2][TN];
-        auto fetch = [&](const unsigned char *cur, int ks, int buf) {
-#pragma unroll
-            for (int i = 0; i < TMV; ++i)
-                a[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + i) * KS + ks) * 1024 + lane * 16);
-            if (TMV > 0) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    b[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((wn * TN + j) * KS + ks) * 1024 + lane * 16);
-            }
+        auto fetch_one = [&](const unsigned char *cur, int ks, int buf, int r) {      // r-th fragment of a k-step
+            // weight fragments first: the MFMAs run over them in the inner loop, so both are needed by the second MFMA
+            if (r < TN) b[buf][r] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((wn * TN + r) * KS + ks) * 1024 + lane * 16);
+            else a[buf][r - TN] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + r - TN) * KS + ks) * 1024 + lane * 16);
+        };
+        auto copy_one = [&](int kt, int stg, int j) {
+            dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
+                                                                         : lds_base + stg * STAGE_BYTES + j * NT * 16);
         };
         int stage = 0, in_slice = 0;
         __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD & 15) | (((NS - 2) * NLOAD >> 4) << 14));
         __builtin_amdgcn_s_barrier();          // the first tile is there
         asm volatile("" ::: "memory");
-        fetch(smem, 0, 0);
-        int pend_kt = 0, pend_stage = 0;       // tile whose later copy slices are still to be issued
-        bool pending = false;
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
+#pragma unroll
+        for (int r = 0; r < NRD; ++r) fetch_one(smem, 0, 0, r);
+        // Tile whose later copy slices are still to be issued.  Before the first barrier of the loop that is the tile
+        // of the one free stage: its slices 1.. are then written twice with the same bytes, which keeps the number of
+        // copies per k-step, and with it every s_waitcnt below, the same in all iterations.
+        int pend_kt = min(kt_begin + NS - 1, last), pend_stage = NS - 1;
+        // One k-tile.  The last one is a separate copy of the code (no barrier, no requests for a next tile), so that the
+        // steady-state loop body is straight-line: at a join of the two paths the compiler's s_waitcnt for the last
+        // k-step's fragments would also wait for the next tile's fragments requested just before it.
+        // Within a k-step the requests for the next k-step are dealt out one per MFMA, in this order and pinned by
+        // scheduling barriers: after the workgroup barrier all eight waves would otherwise send their fragment reads at
+        // once, the LDS queue fills, and the MFMAs behind them in program order start late; left to itself the
+        // scheduler also sinks the reads below the MFMAs to shorten register live ranges and exposes their latency.
+        auto tile = [&](int kt, auto last_tag) {
+            constexpr bool LAST = decltype(last_tag)::value;
             const unsigned char *cur = smem + stage * STAGE_BYTES;
             const int next_stage = stage == NS - 1 ? 0 : stage + 1;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                if (ks == KS - 1) {
-                    if (kt + 1 < kt_end) {
-                        constexpr int NEWER = NS >= 3 ? (NS - 3) * NLOAD : 0;
-                        __builtin_amdgcn_s_waitcnt(0xF70 | (NEWER & 15) | ((NEWER >> 4) << 14));
-                        __builtin_amdgcn_s_barrier();      // tile kt+1 visible to all waves; all waves have left tile kt-1
-                        asm volatile("" ::: "memory");
-                        fetch(smem + next_stage * STAGE_BYTES, 0, 0);
-                        pend_kt = min(kt + NS - 1, last); pend_stage = stage == 0 ? NS - 1 : stage - 1; pending = true;
-                        issue_slice(pend_kt, pend_stage, 0);
-                    } else pending = false;
-                } else {
-                    fetch(cur, ks + 1, (ks + 1) & 1);
-                    if (pending) issue_slice(pend_kt, pend_stage, ks + 1);
+                const bool tail = ks == KS - 1;
+                if (tail && !LAST) {
+                    constexpr int NEWER = NS >= 3 ? (NS - 3) * NLOAD : 0;
+                    __builtin_amdgcn_s_waitcnt(0xF70 | (NEWER & 15) | ((NEWER >> 4) << 14));
+                    __builtin_amdgcn_s_barrier();      // tile kt+1 visible to all waves; all waves have left tile kt-1
+                    asm volatile("" ::: "memory");
+                    pend_kt = min(kt + NS - 1, last); pend_stage = stage == 0 ? NS - 1 : stage - 1;
                 }
+                const unsigned char *fsrc = tail ? smem + next_stage * STAGE_BYTES : cur;
+                const int fks = tail ? 0 : ks + 1, fbuf = tail ? 0 : (ks + 1) & 1, slice = tail ? 0 : ks + 1;
+                const bool requests = !(tail && LAST);
+                if (NMF == 0) {
+                    if (requests) issue_slice(pend_kt, pend_stage, slice);
+                    continue;
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < TMV; ++i)
 #pragma unroll
@@ -242,11 +255,27 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
                         else
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+                        const int slot = i * TN + j;
+                        if (requests) {
+                            if (slot < NRD) fetch_one(fsrc, fks, fbuf, slot);
+                            if (NRD > NMF && slot == NMF - 1) {
+#pragma unroll
+                                for (int r = NMF; r < NRD; ++r) fetch_one(fsrc, fks, fbuf, r);
+                            }
+                            // this slice's copies go with the last MFMAs of the k-step
+                            constexpr int PER = (NLOAD + KS - 1) / KS;
+#pragma unroll
+                            for (int q = 0; q < NLOAD; ++q)
+                                if (q % KS == slice && slot == min(max(NMF - PER + q / KS, 0), NMF - 1)) copy_one(pend_kt, pend_stage, q);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
             }
             stage = next_stage;
             if (SL == 1 && TMV != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
-        }
+        };
+        for (int kt = kt_begin; kt < kt_end - 1; ++kt) tile(kt, std::false_type{});
+        tile(kt_end - 1, std::true_type{});
         if (SL == 1 && TMV != 0) {
             fold();
 #pragma unroll
@@ -432,16 +461,20 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     if (M > 256 && N >= 16384) {
         // 256-row or 288-row tiles (12 waves, 3 x 4), whichever pads M less: T = 1088 is 4 x 288 - 64 but 5 x 256 - 192
         const int pad256 = (M + 255) / 256 * 256, pad288 = (M + 287) / 288 * 288;
-        if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
+        // LM head at many rows: the same 4-wave pipelined kernel (1.10 -> 1.00 ms at T = 1088 against 288x256 tiles of 12 waves)
+        if (epi == EPI_ROWMAX && M > 512) launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        else if (epi == EPI_F32_ROWMAJOR && M > 512) launch_one<2, 2, 4, 4, 4, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        else if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
         else if (M <= 512 && epi == EPI_F32_ROWMAJOR)      // few rows (LM head at T ~ 300): spread the copies over the k-steps
             launch_one<2, 4, 4, 2, 2, EPI_F32_ROWMAJOR, 4, true>(A, W, C, M, N, K, ldc, st);
         else if (M <= 512 && epi == EPI_ROWMAX)
             launch_one<2, 4, 4, 2, 2, EPI_ROWMAX, 4, true>(A, W, C, M, N, K, ldc, st);
         else if (epi == EPI_SILU_FRAG)
-            // gate/up at many rows: k-tiles of 32 in a four-stage ring, copies issued in slices between the k-steps
-            // (same LDS, three tiles in flight instead of one; measured 4% faster than two stages of 64), k loop pipelined
-            // across k-tiles (another 3%; no gain for the narrow shapes or for one wave per SIMD with 128x128 per wave)
-            launch_one<2, 4, 4, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            // gate/up at many rows: 4 waves (2 x 2), one per SIMD, each 128x128 of the 256x256 tile (all 256 accumulator
+            // registers of the wave): 8 fragment reads per 16 MFMAs, a third less LDS traffic per MFMA than 8 waves of
+            // 128x64.  k-tiles of 32 in a four-stage ring, k loop pipelined across k-tiles, requests dealt out one per
+            // MFMA (see k_loop_pipe).  283 -> 251 us per layer at T = 1088 against the 8-wave loop the compiler scheduled.
+            launch_one<2, 2, 4, 4, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
         return;
     }
