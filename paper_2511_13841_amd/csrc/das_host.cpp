@@ -50,12 +50,13 @@ struct das_model {
     std::vector<void *> allocs;             // everything to hipFree
     double *inv_freq = nullptr;
     // KV pool: [layer][page][Hkv][16*D] for K and for V
-    bf16_t *kpool = nullptr, *vpool = nullptr;
+    f16_t *kpool = nullptr, *vpool = nullptr;      // bf16-rounded values in binary16 containers
     size_t layer_elems = 0;
     int *page_table = nullptr;
     // workspaces
     float *h = nullptr, *cs = nullptr, *logits = nullptr, *row_stats = nullptr;
-    bf16_t *xn = nullptr, *q_hi = nullptr, *q_lo = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
+    f16_t *q_h = nullptr;
+    bf16_t *xn = nullptr, *attn = nullptr, *act = nullptr, *xsel = nullptr;
     float *qkv = nullptr;                  // fp32 projections of the pass: rounded to bf16 once, after RoPE
     float *gemm_ws = nullptr;        // slice partials of narrow few-row GEMMs
     size_t gemm_ws_floats = 0;
@@ -257,14 +258,14 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     { ProfScope ps(m, KC_EMBED); launch_embed(pm, m->embed, m->h, dm.d, st); }
     for (int l = 0; l < dm.L; ++l) {
         const LayerW &w = m->layers[l];
-        bf16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
+        f16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
         { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats); }
-        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->q_hi, m->q_lo, m->cs, kl, vl, dm, st); }
+        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->q_h, m->cs, kl, vl, dm, st); }
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)
-                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_hi, m->q_lo, kl, vl, m->part_o, m->part_ml, dm, st);
+                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_h, kl, vl, m->part_o, m->part_ml, dm, st);
         }
         { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_o, m->part_ml, m->attn, dm, st); }
         { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st, m->gemm_ws, m->gemm_ws_floats); }
@@ -395,7 +396,7 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     A(m->page_table, (size_t)c.max_seqs * m->max_pages);
     HIPCHK(hipMemsetAsync(m->page_table, 0, (size_t)c.max_seqs * m->max_pages * sizeof(int), m->st));
     // ---- workspaces (row counts padded to 256 so GEMM tiles may over-read)
-    A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->q_hi, Mp * qd); A(m->q_lo, Mp * qd); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
+    A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->q_h, Mp * qd); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
     A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
     A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs); A(m->d_keys, (size_t)c.max_rows);
     {   // slice partials of the narrow GEMMs when a pass has at most 512 rows: [slices <= 8][rows][widest narrow output]
@@ -758,7 +759,7 @@ static int kv_io(das_model *m, int mode, int32_t seq_id, int32_t layer, int32_t 
     if (hipMalloc((void **)&dk, cnt * 2) != hipSuccess) { (void)hipGetLastError(); return DAS_ERR_NOMEM; }
     if (hipMalloc((void **)&dv, cnt * 2) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(dk); return DAS_ERR_NOMEM; }
     int rc = DAS_OK;
-    bf16_t *kl = m->kpool + (size_t)layer * m->layer_elems, *vl = m->vpool + (size_t)layer * m->layer_elems;
+    f16_t *kl = m->kpool + (size_t)layer * m->layer_elems, *vl = m->vpool + (size_t)layer * m->layer_elems;
     const int *prow = m->page_table + (size_t)slot * m->max_pages;
     auto fail = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
     do {

@@ -20,6 +20,7 @@
 #include <stdint.h>
 
 typedef uint16_t bf16_t;   // raw bf16 bit pattern in memory
+typedef uint16_t f16_t;    // raw IEEE binary16 bit pattern in memory (KV pages, rotated queries)
 
 #define DAS_PAGE 16
 #define DAS_ATTN_CHUNK 2048          // tokens per split-KV work item (absolute-position aligned)
@@ -86,18 +87,19 @@ void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStrea
 // y (fragment order, K = d) = rmsnorm(h[row]) for row = sel ? sel[i] : i, i < n
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st);
 void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, int D, hipStream_t st);
-// qkv: fp32 [T][qkvN] projections; q is rotated and split into two bf16 terms q_hi + q_lo ([T][Hq*D] each);
-// k is rotated, rounded once and scattered into its page; v is rounded once and scattered
-void launch_rope_kv(const PassMeta &pm, const float *qkv, bf16_t *q_hi, bf16_t *q_lo, const float *cs,
-                    bf16_t *kpool_layer, bf16_t *vpool_layer, const DasDims &dm, hipStream_t st);
+// qkv: fp32 [T][qkvN] projections; q is rotated and rounded to binary16 ([T][Hq*D]); k is rotated, rounded once to
+// bf16 and scattered into its page; v is rounded once to bf16 and scattered.  The pages keep those bf16 values in
+// binary16 containers (exact for 2^-17 <= |x| <= 65504; larger magnitudes saturate).
+void launch_rope_kv(const PassMeta &pm, const float *qkv, f16_t *q_h, const float *cs,
+                    f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st);
 // C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
 // ws: fp32 workspace of ws_floats elements for the slice partials of narrow few-row GEMMs (may be null: slower, same result)
 void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
                  float *ws, size_t ws_floats);
 int gemm_slices(int K, int *slice_tiles);
 // split-KV partial attention for the items of one row-block class, then the merge
-void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
-                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, uint16_t *part_o, float *part_ml,
+void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,
+                 const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml,
                  const DasDims &dm, hipStream_t st);
 void launch_attn_merge(const PassMeta &pm, const uint16_t *part_o, const float *part_ml, bf16_t *out_frag,
                        const DasDims &dm, hipStream_t st);
@@ -110,8 +112,9 @@ void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, fl
 void launch_sample(const float *logits, int V, const int *tok, const int *b_row0, const int *b_n, int NB,
                    float inv_temp, const float *u_accept, const float *u_sample, int prefill_mode,
                    float *row_stats, int *accept_len, int *next_token, hipStream_t st);
-void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_t *kpool_layer, bf16_t *vpool_layer,
+// k_lin / v_lin: bf16, linear [n_pos][Hkv][D]; mode 0 imports into the pages, mode 1 exports
+void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, f16_t *kpool_layer, f16_t *vpool_layer,
                   bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, hipStream_t st);
-void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D, int num_pages,
+void launch_kv_synth(const int *page_row, int ctx, f16_t *kpool_layer, f16_t *vpool_layer, int Hkv, int D, int num_pages,
                      uint64_t seed, uint64_t seq_key, int layer, hipStream_t st);
 void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st);

@@ -1,4 +1,7 @@
-// Ragged causal GQA attention over the paged bf16 KV cache (split-KV).
+// Ragged causal GQA attention over the paged KV cache (split-KV).  The cache holds bf16-rounded values in
+// binary16 containers (see rope_kv_kernel): the MFMAs here are the f16 ones, whose 11-bit operands let the rotated
+// query and the probabilities go in as ONE term each (as bf16 each needed a hi + lo pair to keep the scores and the
+// weighted sum at fp32-like accuracy, which doubled the matrix work).
 //
 // One workgroup = one (sequence, KV head, 1024-token chunk).  All G*(1+k_i)
 // query rows that share the KV head are served by ONE pass over the chunk's
@@ -7,7 +10,7 @@
 //   * pages are stored in MFMA operand order, so a 32-token tile (2 pages of K
 //     and of V) is four contiguous runs copied to LDS with coalesced 16-byte
 //     loads, double buffered, and read back lane-linearly (no bank conflicts);
-//   * S^T = K Q^T with v_mfma_f32_16x16x32_bf16 puts 8 tokens of one query row
+//   * S^T = K Q^T with v_mfma_f32_16x16x32_f16 puts 8 tokens of one query row
 //     in each lane, so the row max needs two cross-lane steps and the
 //     probabilities are already laid out as the B operand of O^T += V^T P^T;
 //   * chunks start at absolute multiples of 1024 tokens and each chunk is
@@ -18,8 +21,7 @@
 #include "das_internal.h"
 #include <cstdlib>
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // two floats -> packed fp16 pair (round to nearest even), and back
@@ -44,14 +46,13 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // Two waves per SIMD are asked for whenever the row blocks fit 256 registers: besides the occupancy, it
 // makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
 // without copies out of the accumulation register file on every tile.
-// DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 2 / 3 / 4 without the lo term of
-// q / of p / of both, 6 arithmetic only (no copies after the first two tiles), 7 copies only and no partial stores.
+// DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 6 arithmetic only (no copies after
+// the first two tiles), 7 copies only and no partial stores.
 template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
-                                                           const bf16_t *__restrict__ q_hi,
-                                                           const bf16_t *__restrict__ q_lo,
-                                                           const bf16_t *__restrict__ kpool,
-                                                           const bf16_t *__restrict__ vpool,
+                                                           const f16_t *__restrict__ q_h,
+                                                           const f16_t *__restrict__ kpool,
+                                                           const f16_t *__restrict__ vpool,
                                                            uint16_t *__restrict__ part_o, float *__restrict__ part_ml,
                                                            int Hkv, int G, int qstride, float scale_log2e) {
     constexpr int KFR = D / 32;            // K fragments (1 KiB) per page
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     for (int q = 0; q < NPREG; ++q) my_page[q] = pt[min(first_page + q * 64 + lane, npages - 1)];
 
     // ---- query fragments (B operand: lane l = query row l%16, dims 8*(l/16)..+7 of each 32-dim step)
-    bf16x8 qf[RBW][KFR], ql[RBW][KFR];     // q = qf + ql: two bf16 terms, so the scores see q at ~16 bits
+    f16x8 qf[RBW][KFR];
     int lim[RBW];           // last KV position this lane's query row may see (-1: padding row)
     bool any_active = false;
 #pragma unroll
@@ -101,10 +102,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         const size_t qo = (size_t)(row0 + j) * qstride + (size_t)(kvh * G + g) * D + 8 * (lane >> 4);
 #pragma unroll
         for (int ks = 0; ks < KFR; ++ks) {
-            uint4 v = valid ? *reinterpret_cast<const uint4 *>(q_hi + qo + ks * 32) : make_uint4(0, 0, 0, 0);
-            uint4 w = valid ? *reinterpret_cast<const uint4 *>(q_lo + qo + ks * 32) : make_uint4(0, 0, 0, 0);
-            qf[i][ks] = *reinterpret_cast<bf16x8 *>(&v);
-            ql[i][ks] = *reinterpret_cast<bf16x8 *>(&w);
+            uint4 v = valid ? *reinterpret_cast<const uint4 *>(q_h + qo + ks * 32) : make_uint4(0, 0, 0, 0);
+            qf[i][ks] = *reinterpret_cast<f16x8 *>(&v);
         }
     }
 
@@ -132,14 +131,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             const int u = tid + jn * NT;
             const int seg = u / UNITS_PER_SEG, off = u % UNITS_PER_SEG;
             const int pg = (seg & 1) ? pg1 : pg0;
-            const bf16_t *base = (seg < 2 ? kpool : vpool) + ((size_t)pg * Hkv + kvh) * PAGE_E;
+            const f16_t *base = (seg < 2 ? kpool : vpool) + ((size_t)pg * Hkv + kvh) * PAGE_E;
             dma16(reinterpret_cast<const uint4 *>(base) + off, lds_base + stage * TILE_B + jn * NT * 16 + wave * 1024);
         }
     };
 
     // ---- the three phases of a tile, kept apart so that two tiles can be interleaved below
     struct Scores { f32x4 v[RBW][2]; };
-    struct Probs { bf16x8 hi[RBW], lo[RBW]; };
+    struct Probs { f16x8 v[RBW]; };
 
     // S^T = K Q^T : s[i][pg][r] = score of token 16*pg + 4*(lane/16) + r for query row lane%16
     auto qk = [&](const unsigned char *cur, Scores &s) {
@@ -147,16 +146,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         for (int i = 0; i < RBW; ++i) { s.v[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s.v[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int ks = 0; ks < KFR; ++ks) {
-            const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(cur + (ks * 64 + lane) * 16);
-            const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
+            const f16x8 k0 = *reinterpret_cast<const f16x8 *>(cur + (ks * 64 + lane) * 16);
+            const f16x8 k1 = *reinterpret_cast<const f16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
 #pragma unroll
             for (int i = 0; i < RBW; ++i) {
-                s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[i][ks], s.v[i][0], 0, 0, 0);
-                s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[i][ks], s.v[i][1], 0, 0, 0);
-                if (DBG != 2 && DBG != 4) {
-                s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[i][ks], s.v[i][0], 0, 0, 0);
-                s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[i][ks], s.v[i][1], 0, 0, 0);
-                }
+                s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0, qf[i][ks], s.v[i][0], 0, 0, 0);
+                s.v[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1, qf[i][ks], s.v[i][1], 0, 0, 0);
             }
         }
     };
@@ -199,7 +194,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             }
         }
     };
-    // probabilities of a checked tile, as two bf16 terms (p = hi + lo to ~16 bits), and the row sums
+    // probabilities of a checked tile, rounded to binary16 (at most 256 by the rule above; what falls below the
+    // format's 6e-8 is lost against a row sum of at least 1), and the row sums of the unrounded values
     auto probs = [&](const Scores &s, Probs &p) {
 #pragma unroll
         for (int i = 0; i < RBW; ++i) {
@@ -212,24 +208,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
                 ps += pv[r];
             }
             l_run[i] += ps;
-            // p = hi + lo: round a pair to bf16 with one packed conversion, widen the two halves again by
-            // shift / mask, and convert the remainders the same way
-            uint32_t hu[4], lu[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                typedef __attribute__((ext_vector_type(2))) float f32x2;
-                typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-                const bf16x2 h = __builtin_convertvector((f32x2){pv[2 * r], pv[2 * r + 1]}, bf16x2);
-                hu[r] = *reinterpret_cast<const uint32_t *>(&h);
-                const float ra = pv[2 * r] - __uint_as_float(hu[r] << 16);
-                const float rb = pv[2 * r + 1] - __uint_as_float(hu[r] & 0xFFFF0000u);
-                const bf16x2 l = __builtin_convertvector((f32x2){ra, rb}, bf16x2);
-                lu[r] = *reinterpret_cast<const uint32_t *>(&l);
-            }
             typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-            const u32x4 hv = {hu[0], hu[1], hu[2], hu[3]}, lv = {lu[0], lu[1], lu[2], lu[3]};
-            p.hi[i] = *reinterpret_cast<const bf16x8 *>(&hv);
-            p.lo[i] = *reinterpret_cast<const bf16x8 *>(&lv);
+            const u32x4 hv = {pack_h2(pv[0], pv[1]), pack_h2(pv[2], pv[3]), pack_h2(pv[4], pv[5]), pack_h2(pv[6], pv[7])};
+            p.v[i] = *reinterpret_cast<const f16x8 *>(&hv);
         }
     };
 
@@ -246,12 +227,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             const u32x2 hi = *(lds_u32x2_ptr)(cur + 3 * PAGE_B + (db * 64 + lane) * 8);
             typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
             u32x4 vv = {lo[0], lo[1], hi[0], hi[1]};
-            const bf16x8 vf = *reinterpret_cast<bf16x8 *>(&vv);
+            const f16x8 vf = *reinterpret_cast<f16x8 *>(&vv);
 #pragma unroll
-            for (int i = 0; i < RBW; ++i) {
-                acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.hi[i], acc[i][db], 0, 0, 0);
-                if (DBG != 3 && DBG != 4) acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p.lo[i], acc[i][db], 0, 0, 0);
-            }
+            for (int i = 0; i < RBW; ++i) acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, p.v[i], acc[i][db], 0, 0, 0);
         }
     };
 
@@ -316,8 +294,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     }
 }
 
-void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const bf16_t *q_hi, const bf16_t *q_lo,
-                 const bf16_t *kpool_layer, const bf16_t *vpool_layer, uint16_t *part_o, float *part_ml,
+void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,
+                 const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml,
                  const DasDims &dm, hipStream_t st) {
     if (n_items <= 0) return;
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
@@ -330,13 +308,10 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     // arithmetic separately.  Their results are wrong by design.  Selected by the DAS_ATTN_DBG environment variable.
     const int dbg = getenv("DAS_ATTN_DBG") ? atoi(getenv("DAS_ATTN_DBG")) : 0;
 #define ATTN_LAUNCHD(DD, RB, DG) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     if (dbg && dm.D == 128) {
         switch (dbg * 10 + (rbw <= 2 ? 1 : 2)) {
         case 11: ATTN_LAUNCHD(128, 1, 1); return; case 12: ATTN_LAUNCHD(128, 2, 1); return;
-        case 21: ATTN_LAUNCHD(128, 1, 2); return; case 22: ATTN_LAUNCHD(128, 2, 2); return;
-        case 31: ATTN_LAUNCHD(128, 1, 3); return; case 32: ATTN_LAUNCHD(128, 2, 3); return;
-        case 41: ATTN_LAUNCHD(128, 1, 4); return; case 42: ATTN_LAUNCHD(128, 2, 4); return;
         case 61: ATTN_LAUNCHD(128, 1, 6); return; case 62: ATTN_LAUNCHD(128, 2, 6); return;
         case 71: ATTN_LAUNCHD(128, 1, 7); return; case 72: ATTN_LAUNCHD(128, 2, 7); return;
         }
@@ -344,7 +319,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
 #undef ATTN_LAUNCHD
 #endif
 #define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_hi, q_lo, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
     if (dm.D == 128) {
         if (rbw <= 2) ATTN_LAUNCH(128, 1); else ATTN_LAUNCH(128, 2);

@@ -141,12 +141,23 @@ void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, in
     rope_table_kernel<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(pm.row_pos, inv_freq, reinterpret_cast<float2 *>(cs), pm.T, D / 2);
 }
 
-// ---------------------------------------------------------------- RoPE on q and k; q split hi/lo; K/V rows -> pages
+// ---------------------------------------------------------------- RoPE on q and k; K/V rows -> pages
+// binary16 bit pattern of x, round to nearest even, saturating at the largest finite value
+__device__ __forceinline__ f16_t f2h(float x) {
+    const _Float16 h = (_Float16)fminf(fmaxf(x, -65504.f), 65504.f);
+    return __builtin_bit_cast(f16_t, h);
+}
+__device__ __forceinline__ float h2f(f16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
+// a K or V element: rounded to bf16 exactly once (the cache precision), then kept in a binary16 container, which is
+// exact for every bf16 value with 2^-17 <= |x| <= 65504 (smaller ones move by at most 3e-8, larger ones saturate).
+// The attention kernel's matrix instructions are the f16 ones: next to these values the rotated query and the
+// probabilities then carry 11 significant bits in one term.
+__device__ __forceinline__ f16_t kv_elem(float x) { return f2h(bf2f(f2bf(x))); }
+
 // grid (T, Hq + 2 Hkv), block D/2: thread i owns the rotate-half pair (i, i + D/2).  The projections arrive in
-// fp32 and are rounded to bf16 exactly once, after the rotation.  q keeps a second bf16 term (q - bf16(q)) so
-// that the scores see it at ~16 bits: the attention kernel multiplies K by both terms.
-__global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, bf16_t *__restrict__ q_hi, bf16_t *__restrict__ q_lo,
-                               const float2 *__restrict__ cs, bf16_t *__restrict__ kpool, bf16_t *__restrict__ vpool,
+// fp32 and are rounded exactly once, after the rotation: q to binary16, k and v to bf16.
+__global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, f16_t *__restrict__ q_h,
+                               const float2 *__restrict__ cs, f16_t *__restrict__ kpool, f16_t *__restrict__ vpool,
                                int Hq, int Hkv, int D, int qkvN) {
     int r = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = D >> 1;
     const float *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
@@ -158,33 +169,31 @@ __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, bf16_
     }
     if (hh < Hq) {
         const size_t o = (size_t)r * Hq * D + (size_t)hh * D;
-        const bf16_t h1 = f2bf(x1), h2 = f2bf(x2);
-        q_hi[o + i] = h1; q_hi[o + i + half] = h2;
-        q_lo[o + i] = f2bf(x1 - bf2f(h1)); q_lo[o + i + half] = f2bf(x2 - bf2f(h2));
+        q_h[o + i] = f2h(x1); q_h[o + i + half] = f2h(x2);
         return;
     }
     int b = pm.row_b[r], pos = pm.row_pos[r];
     int page = pm.page_table[(size_t)pm.b_slot[b] * pm.max_pages + (pos >> 4)];
     int t = pos & 15;
     if (hh < Hq + Hkv) {
-        bf16_t *blk = kpool + ((size_t)page * Hkv + (hh - Hq)) * (size_t)(DAS_PAGE * D);
-        blk[kpage_off(t, i)] = f2bf(x1);
-        blk[kpage_off(t, i + half)] = f2bf(x2);
+        f16_t *blk = kpool + ((size_t)page * Hkv + (hh - Hq)) * (size_t)(DAS_PAGE * D);
+        blk[kpage_off(t, i)] = kv_elem(x1);
+        blk[kpage_off(t, i + half)] = kv_elem(x2);
     } else {
-        bf16_t *blk = vpool + ((size_t)page * Hkv + (hh - Hq - Hkv)) * (size_t)(DAS_PAGE * D);
-        blk[vpage_off(t, i)] = f2bf(x1);
-        blk[vpage_off(t, i + half)] = f2bf(x2);
+        f16_t *blk = vpool + ((size_t)page * Hkv + (hh - Hq - Hkv)) * (size_t)(DAS_PAGE * D);
+        blk[vpage_off(t, i)] = kv_elem(x1);
+        blk[vpage_off(t, i + half)] = kv_elem(x2);
     }
 }
-void launch_rope_kv(const PassMeta &pm, const float *qkv, bf16_t *q_hi, bf16_t *q_lo, const float *cs,
-                    bf16_t *kpool_layer, bf16_t *vpool_layer, const DasDims &dm, hipStream_t st) {
+void launch_rope_kv(const PassMeta &pm, const float *qkv, f16_t *q_h, const float *cs,
+                    f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st) {
     rope_kv_kernel<<<dim3(pm.T, dm.Hq + 2 * dm.Hkv), dim3(dm.D / 2), 0, st>>>(
-        pm, qkv, q_hi, q_lo, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
+        pm, qkv, q_h, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
 }
 
 // ---------------------------------------------------------------- KV import / export / synthetic fill
-// linear layout [n_pos][Hkv][D]; grid (n_pos, Hkv), block D
-__global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int first_pos, bf16_t *kpool, bf16_t *vpool,
+// linear layout [n_pos][Hkv][D] in bf16; grid (n_pos, Hkv), block D
+__global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int first_pos, f16_t *kpool, f16_t *vpool,
                              bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages) {
     int p = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
     int pos = first_pos + p;
@@ -192,14 +201,14 @@ __global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int fir
     size_t lin = ((size_t)p * Hkv + hd) * D + d;
     int t = pos & 15;
     if (mode == 0) {
-        kpool[blk + kpage_off(t, d)] = k_lin[lin];
-        vpool[blk + vpage_off(t, d)] = v_lin[lin];
+        kpool[blk + kpage_off(t, d)] = f2h(bf2f(k_lin[lin]));
+        vpool[blk + vpage_off(t, d)] = f2h(bf2f(v_lin[lin]));
     } else {
-        k_lin[lin] = kpool[blk + kpage_off(t, d)];
-        v_lin[lin] = vpool[blk + vpage_off(t, d)];
+        k_lin[lin] = f2bf(h2f(kpool[blk + kpage_off(t, d)]));
+        v_lin[lin] = f2bf(h2f(vpool[blk + vpage_off(t, d)]));
     }
 }
-void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, bf16_t *kpool_layer, bf16_t *vpool_layer,
+void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, f16_t *kpool_layer, f16_t *vpool_layer,
                   bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, hipStream_t st) {
     if (n_pos > 0)
         kv_io_kernel<<<dim3(n_pos, Hkv), dim3(D), 0, st>>>(mode, page_row, first_pos, kpool_layer, vpool_layer, k_lin, v_lin, Hkv, D, num_pages);
@@ -211,12 +220,12 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
-__device__ __forceinline__ bf16_t synth_value(uint64_t base, uint64_t e) {
+__device__ __forceinline__ f16_t synth_value(uint64_t base, uint64_t e) {
     uint64_t h = mix64(base ^ e);
     int s = (int)(h & 0xFFFF) + (int)((h >> 16) & 0xFFFF) + (int)((h >> 32) & 0xFFFF) + (int)(h >> 48) - 131070;
-    return f2bf((float)s * (1.0f / 32768.0f));
+    return kv_elem((float)s * (1.0f / 32768.0f));
 }
-__global__ void kv_synth_kernel(const int *__restrict__ page_row, bf16_t *kpool, bf16_t *vpool, int Hkv, int D, int num_pages,
+__global__ void kv_synth_kernel(const int *__restrict__ page_row, f16_t *kpool, f16_t *vpool, int Hkv, int D, int num_pages,
                                 uint64_t base_k, uint64_t base_v) {
     int pos = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
     size_t blk = ((size_t)page_row[pos >> 4] * Hkv + hd) * (size_t)(DAS_PAGE * D);
@@ -231,7 +240,7 @@ static uint64_t host_mix64(uint64_t z) {
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
-void launch_kv_synth(const int *page_row, int ctx, bf16_t *kpool_layer, bf16_t *vpool_layer, int Hkv, int D, int num_pages,
+void launch_kv_synth(const int *page_row, int ctx, f16_t *kpool_layer, f16_t *vpool_layer, int Hkv, int D, int num_pages,
                      uint64_t seed, uint64_t seq_key, int layer, hipStream_t st) {
     if (ctx <= 0) return;
     uint64_t b = host_mix64(host_mix64(seed ^ 0x4B5653594E544821ull) ^ seq_key);

@@ -61,9 +61,17 @@ def test_kv_synth_import_export_are_bit_exact(das, model):
         np.testing.assert_array_equal(k, di.kv_synth(42, 9, layer, 0, 0, ctx, shape.n_kv_heads, shape.head_dim))
         np.testing.assert_array_equal(v, di.kv_synth(42, 9, layer, 1, 0, ctx, shape.n_kv_heads, shape.head_dim))
     # import a window, read it back, neighbours untouched
+    # (any bf16 pattern with 2^-17 <= |x| < 2^16 minus one ulp: the range the pages hold exactly)
     rng = np.random.default_rng(0)
-    kk = rng.integers(0, 1 << 15, size=(37, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
-    vv = rng.integers(0, 1 << 15, size=(37, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+
+    def patterns():
+        sh = (37, shape.n_kv_heads, shape.head_dim)
+        e = rng.integers(127 - 17, 127 + 16, size=sh)
+        m = rng.integers(0, 128, size=sh)
+        m = np.where(e == 127 + 15, np.minimum(m, 126), m)          # 0x477F = 65280 is the largest bf16 below 65504
+        return ((rng.integers(0, 2, size=sh) << 15) | (e << 7) | m).astype(np.uint16)
+    kk, vv = patterns(), patterns()
+    kk[0, 0, :4] = [0, 0x8000, 0x3F80, 0xBF80]                       # +-0, +-1
     dm.kv_import(5, 1, 100, kk, vv)
     k, v = dm.kv_export(5, 1, 90, 60)
     np.testing.assert_array_equal(k[10:47], kk)
