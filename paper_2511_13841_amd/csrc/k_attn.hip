@@ -40,7 +40,7 @@ __device__ __forceinline__ float2 unpack_h2(uint32_t u) {
 // lds_wave_base + 16*l.  Inline assembly, so that the copies are ordered only by the explicit
 // s_waitcnt/s_barrier of the tile loop (M0 carries the LDS address; 1 wait state before its use).
 __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
 
 // Two waves per SIMD are asked for whenever the row blocks fit 256 registers: besides the occupancy, it
@@ -48,7 +48,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // without copies out of the accumulation register file on every tile.
 // DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 6 arithmetic only (no copies after
 // the first two tiles), 7 copies only and no partial stores.
-template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
+template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0, int TPB = 2>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const f16_t *__restrict__ q_h,
                                                            const f16_t *__restrict__ kpool,
@@ -238,11 +238,37 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     // while this pair is processed.  (Matrix and vector instructions of one SIMD do not overlap on this chip --
     // measured: their times add even with four waves per SIMD -- so nothing is gained by interleaving the score
     // MFMAs of one tile with the exponentials of another; what counts is the instruction count per tile.)
-    static_assert(NS == 4, "two tiles in use, two in flight");
+    const bool work = any_active && DBG != 1 && DBG != 7;
+    if (TPB == 1) {
+        // One tile per barrier, ring of NS stages: tile ti in use, tiles ti+1 .. ti+NS-1 in flight.  Copies are issued
+        // unconditionally (past the end: the last tile again, into a stage nobody reads any more), so "tile ti has
+        // landed" is the same s_waitcnt in every iteration and the copy queue never drains at a barrier.
+        const int last = ntiles - 1;
+#pragma unroll
+        for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(s0, last), s0);
+        int stage = 0;
+        for (int ti = 0; ti < ntiles; ++ti) {
+            constexpr int NEWER = (NS - 2) * NLOAD;
+            __builtin_amdgcn_s_waitcnt(0xF70 | (NEWER & 15) | ((NEWER >> 4) << 14));
+            __builtin_amdgcn_s_barrier();      // tile ti visible to all waves; all waves are done with tile ti-1
+            asm volatile("" ::: "memory");
+            if (DBG != 6) issue(min(ti + NS - 1, last), stage == 0 ? NS - 1 : stage - 1);
+            if (work) {
+                const unsigned char *c0 = smem + stage * TILE_B;
+                Scores s0;
+                Probs p0;
+                qk(c0, s0);
+                row_check(ti, s0);
+                probs(s0, p0);
+                pv(c0, p0);
+            }
+            stage = stage == NS - 1 ? 0 : stage + 1;
+        }
+    } else {
+    static_assert(TPB == 1 || NS == 4, "two tiles in use, two in flight");
     issue(0, 0);
     if (ntiles > 1) issue(1, 1);
     int stage = 0;
-    const bool work = any_active && DBG != 1 && DBG != 7;
     for (int ti = 0; ti < ntiles; ti += 2) {
         __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0)
         __builtin_amdgcn_s_barrier();          // bare barrier: no fence needed, LDS is written by the copies only
@@ -265,6 +291,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             }
         }
         stage ^= 2;
+    }
     }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
@@ -308,7 +335,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
     // arithmetic separately.  Their results are wrong by design.  Selected by the DAS_ATTN_DBG environment variable.
     const int dbg = getenv("DAS_ATTN_DBG") ? atoi(getenv("DAS_ATTN_DBG")) : 0;
 #define ATTN_LAUNCHD(DD, RB, DG) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG, 1><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     if (dbg && dm.D == 128) {
         switch (dbg * 10 + (rbw <= 2 ? 1 : 2)) {
         case 11: ATTN_LAUNCHD(128, 1, 1); return; case 12: ATTN_LAUNCHD(128, 2, 1); return;
@@ -319,7 +346,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
 #undef ATTN_LAUNCHD
 #endif
 #define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
+    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, 0, 1><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
     if (dm.D == 128) {
         if (rbw <= 2) ATTN_LAUNCH(128, 1); else ATTN_LAUNCH(128, 2);
