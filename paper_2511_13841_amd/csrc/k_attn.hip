@@ -48,7 +48,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // without copies out of the accumulation register file on every tile.
 // DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 6 arithmetic only (no copies after
 // the first two tiles), 7 copies only and no partial stores.
-template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0, int TPB = 2>
+template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const f16_t *__restrict__ q_h,
                                                            const f16_t *__restrict__ kpool,
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     constexpr int NLOAD = (TILE_B / 16) / NT;
     static_assert((TILE_B / 16) % NT == 0, "tile must divide over the threads");
     // ring of NS tile stages: one being read, NS-1 being filled
-    __shared__ __align__(16) unsigned char smem[NS * TILE_B];
+    extern __shared__ __align__(16) unsigned char smem[];      // NS * TILE_B bytes
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
     // work items arrive sorted longest first: sequence, chunk | KV head << 20
@@ -233,13 +233,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         }
     };
 
-    // Two tiles per barrier.  Stage ring of NS = 4: tiles ti and ti+1 have landed for every wave (vmcnt(0) before
-    // the barrier) and every wave is done with tiles ti-2 and ti-1, whose stages are refilled with ti+2 and ti+3
-    // while this pair is processed.  (Matrix and vector instructions of one SIMD do not overlap on this chip --
-    // measured: their times add even with four waves per SIMD -- so nothing is gained by interleaving the score
-    // MFMAs of one tile with the exponentials of another; what counts is the instruction count per tile.)
+    // (Matrix and vector instructions of one SIMD do not overlap on this chip -- measured: their times add even with
+    // four waves per SIMD -- so nothing is gained by interleaving the score MFMAs of one tile with the exponentials of
+    // another; what counts is the instruction count per tile.)
     const bool work = any_active && DBG != 1 && DBG != 7;
-    if (TPB == 1) {
+    {
         // One tile per barrier, ring of NS stages: tile ti in use, tiles ti+1 .. ti+NS-1 in flight.  Copies are issued
         // unconditionally (past the end: the last tile again, into a stage nobody reads any more), so "tile ti has
         // landed" is the same s_waitcnt in every iteration and the copy queue never drains at a barrier.
@@ -264,34 +262,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             }
             stage = stage == NS - 1 ? 0 : stage + 1;
         }
-    } else {
-    static_assert(TPB == 1 || NS == 4, "two tiles in use, two in flight");
-    issue(0, 0);
-    if (ntiles > 1) issue(1, 1);
-    int stage = 0;
-    for (int ti = 0; ti < ntiles; ti += 2) {
-        __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0)
-        __builtin_amdgcn_s_barrier();          // bare barrier: no fence needed, LDS is written by the copies only
-        asm volatile("" ::: "memory");
-        if (DBG != 6 && ti + 2 < ntiles) issue(ti + 2, stage ^ 2);
-        if (DBG != 6 && ti + 3 < ntiles) issue(ti + 3, (stage ^ 2) + 1);
-        if (work) {
-            const unsigned char *c0 = smem + stage * TILE_B, *c1 = smem + (stage + 1) * TILE_B;
-            Scores s0;
-            Probs p0;
-            qk(c0, s0);
-            row_check(ti, s0);
-            probs(s0, p0);
-            pv(c0, p0);
-            if (ti + 1 < ntiles) {
-                qk(c1, s0);
-                row_check(ti + 1, s0);
-                probs(s0, p0);
-                pv(c1, p0);
-            }
-        }
-        stage ^= 2;
-    }
     }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
@@ -321,39 +291,50 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     }
 }
 
+// ring depth: four 16 KiB stages per workgroup (one tile in use, three in flight), two workgroups per CU.  Five stages
+// (2 x 80 KiB = all of the CU's LDS) leave room for one workgroup only and are slower (320 against 299 us per layer
+// on contexts of 32k-64k tokens).
+#define DAS_ATTN_STAGES 4
+template <int D, int RBW, int DBG>
+static void launch_attn_cfg(const PassMeta &pm, const int *items, int n_items, const f16_t *q_h, const f16_t *kpool_layer,
+                            const f16_t *vpool_layer, uint16_t *part_o, float *part_ml, const DasDims &dm, float sc, hipStream_t st) {
+    // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
+    // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
+    auto kern = attn_partial_kernel<D, RBW, DAS_ATTN_STAGES, (RBW == 1 ? 4 : 2), 8, DBG>;
+    constexpr int LDS = DAS_ATTN_STAGES * 4 * DAS_PAGE * D * 2;
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        configured = true;
+    }
+    kern<<<dim3(n_items), dim3(512), LDS, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc);
+}
+
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,
                  const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml,
                  const DasDims &dm, hipStream_t st) {
     if (n_items <= 0) return;
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
-    dim3 g(n_items);
-    const size_t lds = 0;     // tile stages are static LDS arrays
-    // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
-    // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
+#define ATTN_ARGS pm, items, n_items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm, sc, st
 #ifdef DAS_ATTN_DEV
     // Development build only (-DDAS_ATTN_DEV): variants that leave parts of the kernel out, to time copies and
     // arithmetic separately.  Their results are wrong by design.  Selected by the DAS_ATTN_DBG environment variable.
     const int dbg = getenv("DAS_ATTN_DBG") ? atoi(getenv("DAS_ATTN_DBG")) : 0;
-#define ATTN_LAUNCHD(DD, RB, DG) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, DG, 1><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     if (dbg && dm.D == 128) {
         switch (dbg * 10 + (rbw <= 2 ? 1 : 2)) {
-        case 11: ATTN_LAUNCHD(128, 1, 1); return; case 12: ATTN_LAUNCHD(128, 2, 1); return;
-        case 61: ATTN_LAUNCHD(128, 1, 6); return; case 62: ATTN_LAUNCHD(128, 2, 6); return;
-        case 71: ATTN_LAUNCHD(128, 1, 7); return; case 72: ATTN_LAUNCHD(128, 2, 7); return;
+        case 11: launch_attn_cfg<128, 1, 1>(ATTN_ARGS); return; case 12: launch_attn_cfg<128, 2, 1>(ATTN_ARGS); return;
+        case 61: launch_attn_cfg<128, 1, 6>(ATTN_ARGS); return; case 62: launch_attn_cfg<128, 2, 6>(ATTN_ARGS); return;
+        case 71: launch_attn_cfg<128, 1, 7>(ATTN_ARGS); return; case 72: launch_attn_cfg<128, 2, 7>(ATTN_ARGS); return;
         }
     }
-#undef ATTN_LAUNCHD
 #endif
-#define ATTN_LAUNCH(DD, RB) \
-    attn_partial_kernel<DD, RB, 4, (RB == 1 ? 4 : 2), 8, 0, 1><<<g, dim3(512), lds, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc)
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
     if (dm.D == 128) {
-        if (rbw <= 2) ATTN_LAUNCH(128, 1); else ATTN_LAUNCH(128, 2);
+        if (rbw <= 2) launch_attn_cfg<128, 1, 0>(ATTN_ARGS); else launch_attn_cfg<128, 2, 0>(ATTN_ARGS);
     } else {
-        if (rbw <= 2) ATTN_LAUNCH(64, 1); else ATTN_LAUNCH(64, 2);
+        if (rbw <= 2) launch_attn_cfg<64, 1, 0>(ATTN_ARGS); else launch_attn_cfg<64, 2, 0>(ATTN_ARGS);
     }
-#undef ATTN_LAUNCH
+#undef ATTN_ARGS
 }
 
 // ---------------------------------------------------------------- merge of the chunk partials
