@@ -192,11 +192,12 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     int *b_prow = p; p += NB;
     int *b_nchunk = p; p += NB;
     int r = 0, n_sel = 0;
+    const int chunk_tokens = das_attn_chunk(dm.Hkv);
     for (int b = 0; b < NB; ++b) {
         const PassBlock &pb = blocks[b];
         b_slot[b] = pb.slot; b_start[b] = pb.start; b_n[b] = pb.n; b_row0[b] = r;
         const int R = dm.G * pb.n, nrb = (R + 15) / 16;
-        const int nchunk = (pb.start + pb.n + DAS_ATTN_CHUNK - 1) / DAS_ATTN_CHUNK;
+        const int nchunk = (pb.start + pb.n + chunk_tokens - 1) / chunk_tokens;
         b_prow[b] = (int)prow; b_nchunk[b] = nchunk;
         prow += (size_t)nchunk * nrb;
         for (int rb = 0; rb < nrb; ++rb) { mblk.push_back(b); mblk.push_back(rb); }
@@ -219,7 +220,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
             for (size_t i = 0; i + 1 < items[c].size(); i += 2) v.push_back({items[c][i], items[c][i + 1] | (h << 20)});
         auto tokens = [&](const std::pair<int, int> &it) {
             const int total = blocks[it.first].start + blocks[it.first].n;
-            return std::min(total - (it.second & 0xFFFFF) * DAS_ATTN_CHUNK, DAS_ATTN_CHUNK);
+            return std::min(total - (it.second & 0xFFFFF) * chunk_tokens, chunk_tokens);
         };
         std::stable_sort(v.begin(), v.end(), [&](const std::pair<int, int> &a, const std::pair<int, int> &b) { return tokens(a) > tokens(b); });
         items[c].resize(2 * v.size());
@@ -247,7 +248,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     pm.b_slot = dptr(b_slot); pm.b_start = dptr(b_start); pm.b_n = dptr(b_n); pm.b_row0 = dptr(b_row0);
     pm.b_prow = dptr(b_prow); pm.b_nchunk = dptr(b_nchunk);
     pm.mblk = dptr(mblk_p); pm.n_mblk = (int)mblk.size() / 2;
-    pm.page_table = m->page_table; pm.max_pages = m->max_pages; pm.num_pages = (int)m->cfg.num_pages;
+    pm.page_table = m->page_table; pm.max_pages = m->max_pages; pm.num_pages = (int)m->cfg.num_pages; pm.chunk = chunk_tokens;
     {
         ProfScope ps(m, KC_META);
         HIPCHK(hipMemcpyAsync(m->d_stage, m->h_stage, used * sizeof(int), hipMemcpyHostToDevice, st));
@@ -409,7 +410,7 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     HIPCHK(hipMemsetAsync(m->act, 0, Mp * Fp * 2, m->st));
     HIPCHK(hipMemsetAsync(m->xsel, 0, Mp * d * 2, m->st));
     // ---- staging
-    const size_t max_items = (size_t)c.max_seqs * (c.max_ctx / DAS_ATTN_CHUNK + 2);
+    const size_t max_items = (size_t)c.max_seqs * (c.max_ctx / das_attn_chunk(c.n_kv_heads) + 2);
     m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)c.max_seqs + 2 * max_items * dm.Hkv +
                     2 * ((size_t)c.max_rows * dm.G / 16 + (size_t)c.max_seqs) +
                     2 * ((size_t)c.max_rows / DAS_PAGE + 2 * (size_t)c.max_seqs + 2) + 64;

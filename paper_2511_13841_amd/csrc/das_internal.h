@@ -23,7 +23,11 @@ typedef uint16_t bf16_t;   // raw bf16 bit pattern in memory
 typedef uint16_t f16_t;    // raw IEEE binary16 bit pattern in memory (KV pages, rotated queries)
 
 #define DAS_PAGE 16
-#define DAS_ATTN_CHUNK 2048          // tokens per split-KV work item (absolute-position aligned)
+#define DAS_ATTN_CHUNK_MAX 2048      // most tokens per split-KV work item (absolute-position aligned); a model uses this or half
+// Tokens per split-KV work item of a model: a function of the model's shape alone (never of a batch), so that a row's
+// reduction order is the same in every pass.  Long chunks halve the partial results to write and merge; with two KV
+// heads a batch has too few (sequence, head, chunk) items to fill the chip at 2048.
+static inline int das_attn_chunk(int n_kv_heads) { return n_kv_heads <= 2 ? DAS_ATTN_CHUNK_MAX / 2 : DAS_ATTN_CHUNK_MAX; }
 #define DAS_ATTN_TILE 32             // tokens per inner tile = 2 pages
 
 enum DasKernelClass {
@@ -73,6 +77,7 @@ struct PassMeta {
     const int *page_table; // [max_seqs][max_pages]
     int max_pages;
     int num_pages;         // pages in the pool
+    int chunk;             // tokens per split-KV chunk (das_attn_chunk of the model)
 };
 
 // EPI_ROWMAX: no matrix is written; every row's (largest value, lowest column holding it) is folded into a 64-bit key per

@@ -74,16 +74,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ctx = pm.b_start[b], n = pm.b_n[b], row0 = pm.b_row0[b];
     const int R = G * n;
-    const int tok_begin = chunk * DAS_ATTN_CHUNK;
+    const int tok_begin = chunk * pm.chunk;
     const int tok_total = ctx + n;
-    const int tok_end = min(tok_begin + DAS_ATTN_CHUNK, tok_total);
+    const int tok_end = min(tok_begin + pm.chunk, tok_total);
     const int ntiles = (tok_end - tok_begin + DAS_ATTN_TILE - 1) / DAS_ATTN_TILE;
     const int npages = (tok_total + DAS_PAGE - 1) / DAS_PAGE;
     const int *pt = pm.page_table + (size_t)pm.b_slot[b] * pm.max_pages;
     // the chunk's (at most 64) page ids, one per lane, fetched once: the tile loop then takes them with
     // v_readlane and never waits on a vector load of its own (which would also wait for every copy in flight)
     const int first_page = tok_begin >> 4;
-    constexpr int NPREG = DAS_ATTN_CHUNK / DAS_PAGE / 64;      // registers of 64 page ids each
+    constexpr int NPREG = DAS_ATTN_CHUNK_MAX / DAS_PAGE / 64;      // registers of 64 page ids each
     int my_page[NPREG];
 #pragma unroll
     for (int q = 0; q < NPREG; ++q) my_page[q] = pt[min(first_page + q * 64 + lane, npages - 1)];
