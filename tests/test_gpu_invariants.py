@@ -17,8 +17,9 @@ def _model(shape, B, max_ctx, pages, max_rows=512, max_draft=16):
                                             num_pages=pages), blob, keep_logits=True)
 
 
-@pytest.mark.parametrize("shape,ctxs", [(di.MODELS["tiny"], [17, 40, 64, 33]), (NARROW_7B, [100, 1020, 2040, 5000])],
-                         ids=["tiny", "7b-heads"])
+@pytest.mark.parametrize("shape,ctxs", [(di.MODELS["tiny"], [17, 40, 64, 33]), (NARROW_7B, [100, 1020, 2040, 5000]),
+                                        (di.MODELS["tiny"], [1000, 1020, 2040, 90])],
+                         ids=["tiny", "7b-heads", "tiny-chunk-boundaries"])
 def test_gpu_speculative_rounds_equal_gpu_plain_decoding(shape, ctxs):
     """The emitted stream of speculative rounds (ragged budgets, a changing batch) is bit-identical to
     one-token-at-a-time decoding on the same engine: every row's result is independent of the batch

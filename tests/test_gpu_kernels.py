@@ -14,7 +14,8 @@ def das():
 
 
 @pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256), (520, 16512, 192), (257, 16384, 64), (560, 16640, 192),
-                                   (40, 320, 1024), (300, 256, 3584), (530, 192, 3136), (64, 128, 16448), (513, 96, 16384)])
+                                   (40, 320, 1024), (300, 256, 3584), (530, 192, 3136), (64, 128, 16448), (513, 96, 16384),
+                                   (600, 16384, 64), (1030, 16448, 320)])
 def test_mfma_gemm_against_fp64(das, M, N, K):
     rng = np.random.default_rng(M * 7 + N)
     a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
@@ -78,4 +79,15 @@ def test_kv_synth_import_export_are_bit_exact(das, model):
     np.testing.assert_array_equal(v[10:47], vv)
     np.testing.assert_array_equal(k[:10], di.kv_synth(42, 9, 1, 0, 90, 10, shape.n_kv_heads, shape.head_dim))
     np.testing.assert_array_equal(v[47:], di.kv_synth(42, 9, 1, 1, 137, 13, shape.n_kv_heads, shape.head_dim))
+    # outside that range: magnitudes above the binary16 maximum saturate at it (65504, which reads back as the bf16
+    # next to it, 65536); magnitudes below 2^-17 move to a multiple of 2^-24 at most 3e-8 away
+    edge = np.zeros((1, shape.n_kv_heads, shape.head_dim), np.float32)
+    edge[0, 0, :6] = [1.0e6, -3.0e38, 65280.0, 2.0 ** -17, 1.0e-6, -2.0 ** -26]
+    eb = di.f32_to_bf16(edge)
+    dm.kv_import(5, 0, 200, eb, eb)
+    k, v = dm.kv_export(5, 0, 200, 1)
+    got = di.bf16_to_f32(k)[0, 0, :6]
+    assert list(got[:4]) == [65536.0, -65536.0, 65280.0, 2.0 ** -17], got
+    assert abs(got[4] - 1.0e-6) <= 3.0e-8 and got[5] == 0.0, got
+    np.testing.assert_array_equal(k, v)
     dm.free()
