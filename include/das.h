@@ -22,7 +22,8 @@
  *    [pending, draft_1 .. draft_k] at positions ctx_len .. ctx_len+k and leaves
  *    the sequence SPECULATIVE; exactly one of das_kv_commit / das_kv_rollback
  *    must follow before the next verify step.
- *  - KV lives in pages of 16 tokens, bf16.  Page ids are handed out from a
+ *  - KV lives in pages of 16 tokens, values rounded to bf16, 2 bytes per element
+ *    (see das_kv_import for the container).  Page ids are handed out from a
  *    stack whose first pop is page 0, in batch order then ascending position;
  *    pages are returned in batch order, highest page position first.
  *  - The library is not thread-safe per model: calls on one das_model must not
@@ -119,7 +120,10 @@ int das_seq_free(das_model *m, int32_t n, const int32_t *seq_ids);
 /* ---- state injection: contexts whose KV is an input rather than a prefill ---- */
 /* New COMMITTED sequence of ctx_len positions (KV contents unspecified until imported) and a pending token. */
 int das_seq_create(das_model *m, int32_t seq_id, int32_t ctx_len, int32_t pending_token);
-/* Copy K and V rows [first_pos, first_pos+n_pos) of one layer; k, v are bf16 [n_pos][n_kv_heads][head_dim]. */
+/* Copy K and V rows [first_pos, first_pos+n_pos) of one layer; k, v are bf16 [n_pos][n_kv_heads][head_dim] in host
+ * memory.  The pages keep bf16-rounded values in 16-bit IEEE binary16 containers: every bf16 value with
+ * 2^-17 <= |x| <= 65280 (and zero) survives an import/export round trip bit for bit; larger magnitudes saturate at
+ * the binary16 maximum 65504, smaller ones move to the nearest multiple of 2^-24 (at most 3e-8 away). */
 int das_kv_import(das_model *m, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos,
                   const uint16_t *k, const uint16_t *v);
 int das_kv_export(das_model *m, int32_t seq_id, int32_t layer, int32_t first_pos, int32_t n_pos,
