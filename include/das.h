@@ -46,7 +46,7 @@ extern "C" {
 typedef struct das_model das_model;   /* opaque: device weights, KV pool, page tables, sequence table, stream */
 
 typedef struct {
-    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim /* 64 or 128 */, d_ffn, vocab;
+    int32_t n_layers, d_model /* multiple of 64, <= 8192 */, n_q_heads, n_kv_heads, head_dim /* 64 or 128 */, d_ffn, vocab;
     float   rope_theta, rms_eps;
     int32_t page_size;      /* must be 16 */
     int32_t max_seqs;       /* sequence slots */

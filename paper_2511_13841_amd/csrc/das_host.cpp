@@ -306,7 +306,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
 
 static int check_config(const das_config *c) {
     if (!c) return DAS_ERR_INVALID;
-    if (c->n_layers < 1 || c->d_model < 64 || c->d_model % 64 || c->n_q_heads < 1 || c->n_kv_heads < 1 ||
+    if (c->n_layers < 1 || c->d_model < 64 || c->d_model % 64 || c->d_model > 8192 || c->n_q_heads < 1 || c->n_kv_heads < 1 ||
         c->n_q_heads % c->n_kv_heads || (c->head_dim != 64 && c->head_dim != 128) || c->d_ffn < 8 || c->d_ffn % 8 ||
         c->vocab < 2 || !(c->rope_theta > 0.f) || !(c->rms_eps > 0.f))
         return DAS_ERR_INVALID;

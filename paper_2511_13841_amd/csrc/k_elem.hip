@@ -92,35 +92,50 @@ void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStrea
 // ---------------------------------------------------------------- RMSNorm -> bf16, fragment order
 // y = x * rsqrt(mean(x^2) + eps) * g, fp32 accumulation; output row i of the
 // fragment-ordered matrix [n][d] comes from h[sel ? sel[i] : i].
+// One wave per row, four rows per workgroup: the row stays in registers between the two passes, the sum needs no
+// LDS or barrier, and the four 16-byte pieces that share a 64-byte line of the fragment layout (rows 4q .. 4q+3) leave
+// the same workgroup together.  The order of the sum depends on d alone.
+template <int MAXC>      // 8-element groups per lane the registers can hold: d <= MAXC * 512
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ y, const int *__restrict__ sel, int d, float eps) {
-    __shared__ float red[4];
-    int i = blockIdx.x;
+                                                      bf16_t *__restrict__ y, const int *__restrict__ sel, int n, int d, float eps) {
+    const int lane = threadIdx.x & 63, i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n) return;
     const float *x = h + (size_t)(sel ? sel[i] : i) * d;
+    const int nc = d / 8;
+    float4 a[MAXC], b[MAXC];
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d / 8; c += 256) {
-        float4 a = reinterpret_cast<const float4 *>(x)[2 * c], b = reinterpret_cast<const float4 *>(x)[2 * c + 1];
-        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+#pragma unroll
+    for (int q = 0; q < MAXC; ++q) {
+        const int c = lane + q * 64;
+        if (c < nc) {
+            a[q] = reinterpret_cast<const float4 *>(x)[2 * c]; b[q] = reinterpret_cast<const float4 *>(x)[2 * c + 1];
+            ss += a[q].x * a[q].x + a[q].y * a[q].y + a[q].z * a[q].z + a[q].w * a[q].w
+                + b[q].x * b[q].x + b[q].y * b[q].y + b[q].z * b[q].z + b[q].w * b[q].w;
+        }
     }
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    float tot = red[0] + red[1] + red[2] + red[3];
-    float inv = rsqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x; c < d / 8; c += 256) {
-        float4 a = reinterpret_cast<const float4 *>(x)[2 * c], b = reinterpret_cast<const float4 *>(x)[2 * c + 1];
-        uint4 gv = reinterpret_cast<const uint4 *>(g)[c];
-        const bf16_t *ge = reinterpret_cast<const bf16_t *>(&gv);
-        bf16_t o[8];
-        o[0] = f2bf(a.x * inv * bf2f(ge[0])); o[1] = f2bf(a.y * inv * bf2f(ge[1]));
-        o[2] = f2bf(a.z * inv * bf2f(ge[2])); o[3] = f2bf(a.w * inv * bf2f(ge[3]));
-        o[4] = f2bf(b.x * inv * bf2f(ge[4])); o[5] = f2bf(b.y * inv * bf2f(ge[5]));
-        o[6] = f2bf(b.z * inv * bf2f(ge[6])); o[7] = f2bf(b.w * inv * bf2f(ge[7]));
-        *reinterpret_cast<uint4 *>(y + frag_off(i, c * 8, d)) = *reinterpret_cast<uint4 *>(o);
+    const float inv = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int q = 0; q < MAXC; ++q) {
+        const int c = lane + q * 64;
+        if (c < nc) {
+            uint4 gv = reinterpret_cast<const uint4 *>(g)[c];
+            const bf16_t *ge = reinterpret_cast<const bf16_t *>(&gv);
+            bf16_t o[8];
+            o[0] = f2bf(a[q].x * inv * bf2f(ge[0])); o[1] = f2bf(a[q].y * inv * bf2f(ge[1]));
+            o[2] = f2bf(a[q].z * inv * bf2f(ge[2])); o[3] = f2bf(a[q].w * inv * bf2f(ge[3]));
+            o[4] = f2bf(b[q].x * inv * bf2f(ge[4])); o[5] = f2bf(b[q].y * inv * bf2f(ge[5]));
+            o[6] = f2bf(b[q].z * inv * bf2f(ge[6])); o[7] = f2bf(b[q].w * inv * bf2f(ge[7]));
+            *reinterpret_cast<uint4 *>(y + frag_off(i, c * 8, d)) = *reinterpret_cast<uint4 *>(o);
+        }
     }
 }
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
-    if (n > 0) rmsnorm_kernel<<<dim3(n), dim3(256), 0, st>>>(h, g, y, sel, d, eps);
+    if (n <= 0) return;
+    const dim3 grid((n + 3) / 4), block(256);
+    if (d <= 2048) rmsnorm_kernel<4><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
+    else if (d <= 4096) rmsnorm_kernel<8><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
+    else rmsnorm_kernel<16><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);      // d <= 8192 (checked at model load)
 }
 
 // ---------------------------------------------------------------- RoPE angles, once per pass
