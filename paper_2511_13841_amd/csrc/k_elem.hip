@@ -169,12 +169,14 @@ __device__ __forceinline__ float h2f(f16_t u) { return (float)__builtin_bit_cast
 // probabilities then carry 11 significant bits in one term.
 __device__ __forceinline__ f16_t kv_elem(float x) { return f2h(bf2f(f2bf(x))); }
 
-// grid (T, Hq + 2 Hkv), block D/2: thread i owns the rotate-half pair (i, i + D/2).  The projections arrive in
-// fp32 and are rounded exactly once, after the rotation: q to binary16, k and v to bf16.
+// grid (T, heads / heads per workgroup), block 256 = 256 / (D/2) heads: thread i of a head owns the rotate-half pair
+// (i, i + D/2).  The projections arrive in fp32 and are rounded exactly once, after the rotation: q to binary16, k and
+// v to bf16.
 __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, f16_t *__restrict__ q_h,
                                const float2 *__restrict__ cs, f16_t *__restrict__ kpool, f16_t *__restrict__ vpool,
                                int Hq, int Hkv, int D, int qkvN) {
-    int r = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = D >> 1;
+    const int half = D >> 1, r = blockIdx.x, hh = blockIdx.y * (256 / half) + threadIdx.x / half, i = threadIdx.x % half;
+    if (hh >= Hq + 2 * Hkv) return;
     const float *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
     float x1 = row[i], x2 = row[i + half];
     if (hh < Hq + Hkv) {
@@ -202,7 +204,8 @@ __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, f16_t
 }
 void launch_rope_kv(const PassMeta &pm, const float *qkv, f16_t *q_h, const float *cs,
                     f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st) {
-    rope_kv_kernel<<<dim3(pm.T, dm.Hq + 2 * dm.Hkv), dim3(dm.D / 2), 0, st>>>(
+    const int heads_per_wg = 256 / (dm.D / 2);
+    rope_kv_kernel<<<dim3(pm.T, (dm.Hq + 2 * dm.Hkv + heads_per_wg - 1) / heads_per_wg), dim3(256), 0, st>>>(
         pm, qkv, q_h, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
 }
 
