@@ -92,50 +92,72 @@ void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStrea
 // ---------------------------------------------------------------- RMSNorm -> bf16, fragment order
 // y = x * rsqrt(mean(x^2) + eps) * g, fp32 accumulation; output row i of the
 // fragment-ordered matrix [n][d] comes from h[sel ? sel[i] : i].
-// One wave per row, four rows per workgroup: the row stays in registers between the two passes, the sum needs no
-// LDS or barrier, and the four 16-byte pieces that share a 64-byte line of the fragment layout (rows 4q .. 4q+3) leave
-// the same workgroup together.  The order of the sum depends on d alone.
-template <int MAXC>      // 8-element groups per lane the registers can hold: d <= MAXC * 512
+// Two launch shapes with the same arithmetic: four rows per workgroup, one wave each (many rows: the row stays in
+// registers between the two passes, no LDS, no barrier, and the four 16-byte pieces that share a 64-byte line of the
+// fragment layout leave the same workgroup together), or one row per workgroup spread over four waves (few rows: four
+// times the loads in flight per row).  Lane l owns the 8-element groups c = l + 64 q; its sum of squares is
+// ((s_0 + s_1) + s_2) + s_3 with s_w the sum over q = w, w + 4, ... in ascending order, then a butterfly over the
+// lanes: the order depends on d alone, so a row's bits do not depend on how many rows the pass has.
+template <int MAXC, int WPR>      // 8-element groups per lane the registers can hold (d <= MAXC * 512); waves per row
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, const bf16_t *__restrict__ g,
                                                       bf16_t *__restrict__ y, const int *__restrict__ sel, int n, int d, float eps) {
-    const int lane = threadIdx.x & 63, i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    static_assert(MAXC % 4 == 0 && (WPR == 1 || WPR == 4), "four partial sums per lane");
+    __shared__ float part[WPR == 4 ? 4 * 64 : 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = WPR == 4 ? blockIdx.x : blockIdx.x * 4 + wave;
     if (i >= n) return;
     const float *x = h + (size_t)(sel ? sel[i] : i) * d;
     const int nc = d / 8;
-    float4 a[MAXC], b[MAXC];
-    float ss = 0.f;
+    constexpr int NQ = MAXC / WPR;                 // groups this thread holds: q = q0 + QS * t
+    const int q0 = WPR == 4 ? wave : 0;
+    constexpr int QS = WPR == 4 ? 4 : 1;
+    float4 a[NQ], b[NQ];
+    float s4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int q = 0; q < MAXC; ++q) {
-        const int c = lane + q * 64;
+    for (int t = 0; t < NQ; ++t) {
+        const int q = q0 + QS * t, c = lane + q * 64;
         if (c < nc) {
-            a[q] = reinterpret_cast<const float4 *>(x)[2 * c]; b[q] = reinterpret_cast<const float4 *>(x)[2 * c + 1];
-            ss += a[q].x * a[q].x + a[q].y * a[q].y + a[q].z * a[q].z + a[q].w * a[q].w
-                + b[q].x * b[q].x + b[q].y * b[q].y + b[q].z * b[q].z + b[q].w * b[q].w;
+            a[t] = reinterpret_cast<const float4 *>(x)[2 * c]; b[t] = reinterpret_cast<const float4 *>(x)[2 * c + 1];
+            s4[WPR == 4 ? 0 : (t & 3)] += a[t].x * a[t].x + a[t].y * a[t].y + a[t].z * a[t].z + a[t].w * a[t].w
+                                        + b[t].x * b[t].x + b[t].y * b[t].y + b[t].z * b[t].z + b[t].w * b[t].w;
         }
+    }
+    float ss;
+    if (WPR == 4) {
+        part[wave * 64 + lane] = s4[0];
+        __syncthreads();
+        ss = ((part[lane] + part[64 + lane]) + part[128 + lane]) + part[192 + lane];
+    } else {
+        ss = ((s4[0] + s4[1]) + s4[2]) + s4[3];
     }
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
     const float inv = rsqrtf(ss / (float)d + eps);
 #pragma unroll
-    for (int q = 0; q < MAXC; ++q) {
-        const int c = lane + q * 64;
+    for (int t = 0; t < NQ; ++t) {
+        const int q = q0 + QS * t, c = lane + q * 64;
         if (c < nc) {
             uint4 gv = reinterpret_cast<const uint4 *>(g)[c];
             const bf16_t *ge = reinterpret_cast<const bf16_t *>(&gv);
             bf16_t o[8];
-            o[0] = f2bf(a[q].x * inv * bf2f(ge[0])); o[1] = f2bf(a[q].y * inv * bf2f(ge[1]));
-            o[2] = f2bf(a[q].z * inv * bf2f(ge[2])); o[3] = f2bf(a[q].w * inv * bf2f(ge[3]));
-            o[4] = f2bf(b[q].x * inv * bf2f(ge[4])); o[5] = f2bf(b[q].y * inv * bf2f(ge[5]));
-            o[6] = f2bf(b[q].z * inv * bf2f(ge[6])); o[7] = f2bf(b[q].w * inv * bf2f(ge[7]));
+            o[0] = f2bf(a[t].x * inv * bf2f(ge[0])); o[1] = f2bf(a[t].y * inv * bf2f(ge[1]));
+            o[2] = f2bf(a[t].z * inv * bf2f(ge[2])); o[3] = f2bf(a[t].w * inv * bf2f(ge[3]));
+            o[4] = f2bf(b[t].x * inv * bf2f(ge[4])); o[5] = f2bf(b[t].y * inv * bf2f(ge[5]));
+            o[6] = f2bf(b[t].z * inv * bf2f(ge[6])); o[7] = f2bf(b[t].w * inv * bf2f(ge[7]));
             *reinterpret_cast<uint4 *>(y + frag_off(i, c * 8, d)) = *reinterpret_cast<uint4 *>(o);
         }
     }
 }
+template <int WPR>
+static void launch_rmsnorm_shape(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
+    const dim3 grid(WPR == 4 ? n : (n + 3) / 4), block(256);
+    if (d <= 2048) rmsnorm_kernel<4, WPR><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
+    else if (d <= 4096) rmsnorm_kernel<8, WPR><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
+    else rmsnorm_kernel<16, WPR><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);      // d <= 8192 (checked at model load)
+}
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
     if (n <= 0) return;
-    const dim3 grid((n + 3) / 4), block(256);
-    if (d <= 2048) rmsnorm_kernel<4><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
-    else if (d <= 4096) rmsnorm_kernel<8><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
-    else rmsnorm_kernel<16><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);      // d <= 8192 (checked at model load)
+    if (n >= 1024) launch_rmsnorm_shape<1>(h, g, y, sel, n, d, eps, st);
+    else launch_rmsnorm_shape<4>(h, g, y, sel, n, d, eps, st);
 }
 
 // ---------------------------------------------------------------- RoPE angles, once per pass

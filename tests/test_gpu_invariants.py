@@ -70,6 +70,41 @@ def test_gpu_speculative_rounds_equal_gpu_plain_decoding(shape, ctxs):
     dm.free()
 
 
+@pytest.mark.parametrize("shape", [di.MODELS["tiny"], NARROW_7B], ids=["tiny", "7b-heads"])
+def test_logit_rows_do_not_depend_on_the_size_of_the_pass(shape):
+    """The logits of a sequence's rows are the same bits whether it is verified alone (16 rows), in a batch of 13
+    (208 rows), of 40 (640 rows) or of 70 (1120 rows): every launch-shape threshold of the row-wise kernels and of the
+    GEMMs (64, 256, 512, 1024 rows) lies between those sizes, and none of them may change a reduction order."""
+    B, k = 70, 15
+    rng = np.random.default_rng(11)
+    ctxs = rng.integers(20, 400, size=B)
+    ctxs[:3] = [1030, 2050, 100]                                   # the sequences compared; two cross a chunk boundary
+    das, dm = _model(shape, B, int(ctxs.max()) + 64, int(sum(-(-(int(c) + 32) // 16) for c in ctxs)) + 4,
+                     max_rows=B * (k + 1), max_draft=k)
+    ids = list(range(B))
+    pend = rng.integers(0, shape.vocab, size=B, dtype=np.int32)
+    for i in ids:
+        dm.seq_create(i, int(ctxs[i]), int(pend[i]))
+        dm.kv_synth(i, 5, i)
+    drafts = [rng.integers(0, shape.vocab, size=k, dtype=np.int32) for _ in ids]
+    ref = {}
+    for nb in (B, 40, 13, 1):
+        sub = ids[:nb] if nb > 3 else ids[:3][:nb]
+        print("pass of", nb, "sequences", flush=True)
+        passes = [sub] if nb > 1 else [[0], [1], [2]]               # alone: one pass per compared sequence
+        for p in passes:
+            dm.verify_step(p, ctxs[p], [drafts[i] for i in p])
+            for j, i in enumerate(p):
+                if i < 3:
+                    got = dm.debug_logits(j * (k + 1), k + 1)
+                    if i in ref:
+                        assert np.array_equal(got, ref[i]), (nb, i, float(np.abs(got - ref[i]).max()))
+                    else:
+                        ref[i] = got
+            dm.kv_rollback(p)
+    dm.free()
+
+
 def test_rollback_reverify_and_fresh_prefill_equivalence():
     shape = di.MODELS["tiny"]
     das, dm = _model(shape, 4, 512, 64)
