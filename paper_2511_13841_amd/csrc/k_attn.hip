@@ -295,19 +295,19 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
 // (2 x 80 KiB = all of the CU's LDS) leave room for one workgroup only and are slower (320 against 299 us per layer
 // on contexts of 32k-64k tokens).
 #define DAS_ATTN_STAGES 4
-template <int D, int RBW, int DBG>
+template <int D, int RBW, int DBG, int NW = 8>
 static void launch_attn_cfg(const PassMeta &pm, const int *items, int n_items, const f16_t *q_h, const f16_t *kpool_layer,
                             const f16_t *vpool_layer, uint16_t *part_o, float *part_ml, const DasDims &dm, float sc, hipStream_t st) {
     // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
     // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
-    auto kern = attn_partial_kernel<D, RBW, DAS_ATTN_STAGES, (RBW == 1 ? 4 : 2), 8, DBG>;
+    auto kern = attn_partial_kernel<D, RBW, DAS_ATTN_STAGES, (RBW == 1 ? 4 : 2), NW, DBG>;
     constexpr int LDS = DAS_ATTN_STAGES * 4 * DAS_PAGE * D * 2;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
     }
-    kern<<<dim3(n_items), dim3(512), LDS, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc);
+    kern<<<dim3(n_items), dim3(NW * 64), LDS, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc);
 }
 
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,
@@ -330,7 +330,9 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
 #endif
     // rbw is the class of the launch: 2 = up to 8 row blocks per KV head, 4 = up to 16
     if (dm.D == 128) {
-        if (rbw <= 2) launch_attn_cfg<128, 1, 0>(ATTN_ARGS); else launch_attn_cfg<128, 2, 0>(ATTN_ARGS);
+        // up to 16 row blocks at head dim 128: 16 waves with one block each (one workgroup per CU, the register and
+        // arithmetic budget of two 8-wave workgroups) rather than 8 waves with two blocks each
+        if (rbw <= 2) launch_attn_cfg<128, 1, 0>(ATTN_ARGS); else launch_attn_cfg<128, 1, 0, 16>(ATTN_ARGS);
     } else {
         if (rbw <= 2) launch_attn_cfg<64, 1, 0>(ATTN_ARGS); else launch_attn_cfg<64, 2, 0>(ATTN_ARGS);
     }
