@@ -257,10 +257,13 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         launch_rope_table(pm, m->inv_freq, m->cs, dm.D, st);
     }
     { ProfScope ps(m, KC_EMBED); launch_embed(pm, m->embed, m->h, dm.d, st); }
+    // A residual GEMM whose K slices are summed by a second kernel (passes of a few hundred rows) lets that kernel
+    // normalise the finished rows as well: xn_ready says that the next RMSNorm has already been done.
+    bool xn_ready = false;
     for (int l = 0; l < dm.L; ++l) {
         const LayerW &w = m->layers[l];
         f16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
-        { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
+        if (!xn_ready) { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
         { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats); }
         { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->q_h, m->cs, kl, vl, dm, st); }
         {
@@ -269,10 +272,20 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
                 launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_h, kl, vl, m->part_o, m->part_ml, dm, st);
         }
         { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_o, m->part_ml, m->attn, dm, st); }
-        { ProfScope ps(m, KC_GEMM_O); launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st, m->gemm_ws, m->gemm_ws_floats); }
-        { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g2, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
+        {
+            const GemmNormTail post_attn = {w.g2, m->xn, dm.rms_eps};
+            ProfScope ps(m, KC_GEMM_O);
+            xn_ready = launch_gemm(EPI_RESID_F32, m->attn, w.wo, m->h, T, dm.d, dm.Hq * dm.D, dm.d, st, m->gemm_ws, m->gemm_ws_floats, &post_attn);
+        }
+        if (!xn_ready) { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g2, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
         { ProfScope ps(m, KC_GEMM_GATEUP); launch_gemm(EPI_SILU_FRAG, m->xn, w.wgu, m->act, T, 2 * dm.Fp, dm.d, dm.Fp, st, m->gemm_ws, m->gemm_ws_floats); }
-        { ProfScope ps(m, KC_GEMM_DOWN); launch_gemm(EPI_RESID_F32, m->act, w.wd, m->h, T, dm.d, dm.Fp, dm.d, st, m->gemm_ws, m->gemm_ws_floats); }
+        {
+            // the next layer's input norm; the final norm gathers the rows that get logits and stays a kernel of its own
+            const GemmNormTail next_input = {l + 1 < dm.L ? m->layers[l + 1].g1 : nullptr, m->xn, dm.rms_eps};
+            ProfScope ps(m, KC_GEMM_DOWN);
+            xn_ready = launch_gemm(EPI_RESID_F32, m->act, w.wd, m->h, T, dm.d, dm.Fp, dm.d, st, m->gemm_ws, m->gemm_ws_floats,
+                                   l + 1 < dm.L ? &next_input : nullptr);
+        }
     }
     if (n_sel > 0) {
         { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, m->gf, m->xsel, pm.sel, n_sel, dm.d, dm.rms_eps, st); }

@@ -91,6 +91,11 @@ void launch_pt_update(int *page_table, const int *upd, int n_upd, hipStream_t st
 void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStream_t st);
 // y (fragment order, K = d) = rmsnorm(h[row]) for row = sel ? sel[i] : i, i < n
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st);
+void launch_reduce_resid_rmsnorm(const float *ws, int slices, float *h, const bf16_t *g, bf16_t *y, int n, int d, float eps, hipStream_t st);
+// RMSNorm that follows a residual GEMM (EPI_RESID_F32): when the GEMM's K slices are summed by a second kernel anyway, that
+// kernel also normalises the finished rows (gain g, output y in fragment order) and launch_gemm returns true; otherwise the
+// caller runs launch_rmsnorm itself.  Same bits either way.
+struct GemmNormTail { const bf16_t *g; bf16_t *y; float eps; };
 void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, int D, hipStream_t st);
 // qkv: fp32 [T][qkvN] projections; q is rotated and rounded to binary16 ([T][Hq*D]); k is rotated, rounded once to
 // bf16 and scattered into its page; v is rounded once to bf16 and scattered.  The pages keep those bf16 values in
@@ -99,8 +104,8 @@ void launch_rope_kv(const PassMeta &pm, const float *qkv, f16_t *q_h, const floa
                     f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st);
 // C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
 // ws: fp32 workspace of ws_floats elements for the slice partials of narrow few-row GEMMs (may be null: slower, same result)
-void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats);
+bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
+                 float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr);
 int gemm_slices(int K, int *slice_tiles);
 // split-KV partial attention for the items of one row-block class, then the merge
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,

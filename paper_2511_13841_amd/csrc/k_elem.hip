@@ -98,15 +98,20 @@ void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStrea
 // times the loads in flight per row).  Lane l owns the 8-element groups c = l + 64 q; its sum of squares is
 // ((s_0 + s_1) + s_2) + s_3 with s_w the sum over q = w, w + 4, ... in ascending order, then a butterfly over the
 // lanes: the order depends on d alone, so a row's bits do not depend on how many rows the pass has.
-template <int MAXC, int WPR>      // 8-element groups per lane the registers can hold (d <= MAXC * 512); waves per row
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ y, const int *__restrict__ sel, int n, int d, float eps) {
+// FUSED: the row is first produced here, as the tail of a GEMM whose K slices went to separate workgroups: the slice
+// partials ws[slices][n][d] are added in ascending order, the sum is added to the residual row h[i] (which is written
+// back), and the new row is normalised -- the arithmetic of gemm_reduce_kernel<EPI_RESID_F32> followed by this kernel,
+// bit for bit, in one launch instead of two.
+template <int MAXC, int WPR, bool FUSED = false>      // 8-element groups per lane the registers can hold (d <= MAXC * 512); waves per row
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const bf16_t *__restrict__ g,
+                                                      bf16_t *__restrict__ y, const int *__restrict__ sel, int n, int d, float eps,
+                                                      const float4 *__restrict__ ws = nullptr, int slices = 0, size_t slab4 = 0) {
     static_assert(MAXC % 4 == 0 && (WPR == 1 || WPR == 4), "four partial sums per lane");
     __shared__ float part[WPR == 4 ? 4 * 64 : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = WPR == 4 ? blockIdx.x : blockIdx.x * 4 + wave;
     if (i >= n) return;
-    const float *x = h + (size_t)(sel ? sel[i] : i) * d;
+    float *x = h + (size_t)((!FUSED && sel) ? sel[i] : i) * d;
     const int nc = d / 8;
     constexpr int NQ = MAXC / WPR;                 // groups this thread holds: q = q0 + QS * t
     const int q0 = WPR == 4 ? wave : 0;
@@ -118,6 +123,18 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
         const int q = q0 + QS * t, c = lane + q * 64;
         if (c < nc) {
             a[t] = reinterpret_cast<const float4 *>(x)[2 * c]; b[t] = reinterpret_cast<const float4 *>(x)[2 * c + 1];
+            if (FUSED) {
+                const float4 *p = ws + (size_t)i * (d / 4) + 2 * c;
+                float4 ta = p[0], tb = p[1];
+                for (int s2 = 1; s2 < slices; ++s2) {
+                    const float4 va = p[(size_t)s2 * slab4], vb = p[(size_t)s2 * slab4 + 1];
+                    ta.x += va.x; ta.y += va.y; ta.z += va.z; ta.w += va.w;
+                    tb.x += vb.x; tb.y += vb.y; tb.z += vb.z; tb.w += vb.w;
+                }
+                a[t].x += ta.x; a[t].y += ta.y; a[t].z += ta.z; a[t].w += ta.w;
+                b[t].x += tb.x; b[t].y += tb.y; b[t].z += tb.z; b[t].w += tb.w;
+                reinterpret_cast<float4 *>(x)[2 * c] = a[t]; reinterpret_cast<float4 *>(x)[2 * c + 1] = b[t];
+            }
             s4[WPR == 4 ? 0 : (t & 3)] += a[t].x * a[t].x + a[t].y * a[t].y + a[t].z * a[t].z + a[t].w * a[t].w
                                         + b[t].x * b[t].x + b[t].y * b[t].y + b[t].z * b[t].z + b[t].w * b[t].w;
         }
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
     }
 }
 template <int WPR>
-static void launch_rmsnorm_shape(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
+static void launch_rmsnorm_shape(float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
     const dim3 grid(WPR == 4 ? n : (n + 3) / 4), block(256);
     if (d <= 2048) rmsnorm_kernel<4, WPR><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
     else if (d <= 4096) rmsnorm_kernel<8, WPR><<<grid, block, 0, st>>>(h, g, y, sel, n, d, eps);
@@ -156,8 +173,19 @@ static void launch_rmsnorm_shape(const float *h, const bf16_t *g, bf16_t *y, con
 }
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st) {
     if (n <= 0) return;
-    if (n >= 1024) launch_rmsnorm_shape<1>(h, g, y, sel, n, d, eps, st);
-    else launch_rmsnorm_shape<4>(h, g, y, sel, n, d, eps, st);
+    float *hh = const_cast<float *>(h);      // only the FUSED instantiation writes through it
+    if (n >= 1024) launch_rmsnorm_shape<1>(hh, g, y, sel, n, d, eps, st);
+    else launch_rmsnorm_shape<4>(hh, g, y, sel, n, d, eps, st);
+}
+// h[i] += sum of the slice partials ws[s][i] (ascending s), then y = rmsnorm(h[i]) in fragment order; n < 1024 rows
+void launch_reduce_resid_rmsnorm(const float *ws, int slices, float *h, const bf16_t *g, bf16_t *y, int n, int d, float eps, hipStream_t st) {
+    if (n <= 0) return;
+    const dim3 grid(n), block(256);
+    const float4 *w4 = reinterpret_cast<const float4 *>(ws);
+    const size_t slab4 = (size_t)n * d / 4;
+    if (d <= 2048) rmsnorm_kernel<4, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4);
+    else if (d <= 4096) rmsnorm_kernel<8, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4);
+    else rmsnorm_kernel<16, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4);
 }
 
 // ---------------------------------------------------------------- RoPE angles, once per pass

@@ -439,9 +439,9 @@ static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int 
 // A must be allocated for M rounded up to 256 rows, W for N rounded up to 256 rows; K % 64 == 0.
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
-void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats) {
-    if (M <= 0) return;
+bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
+                 float *ws, size_t ws_floats, const GemmNormTail *tail) {
+    if (M <= 0) return false;
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
     //  * wide outputs (gate/up, LM head): 256x256, 8 waves (2 x 4) of 128x64 -- half the bytes per flop of a
     //    128x128 tile through the HBM->LDS copy path, which is what saturates first;
@@ -459,7 +459,7 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // seven stages of 22 KiB (six tiles in flight per CU): 121 -> 106 us per layer at T = 272
         else if (M > 192) launch_one<1, 4, 3, 2, 7, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else launch_one<3, 2, 1, 2, 5, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
-        return;
+        return false;
     }
     if (M > 256 && N >= 16384) {
         // 256-row or 288-row tiles (12 waves, 3 x 4), whichever pads M less: T = 1088 is 4 x 288 - 64 but 5 x 256 - 192
@@ -479,16 +479,16 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             // MFMA (see k_loop_pipe).  283 -> 251 us per layer at T = 1088 against the 8-wave loop the compiler scheduled.
             launch_one<2, 2, 4, 4, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
-        return;
+        return false;
     }
     if (epi == EPI_SILU_FRAG) {
         if (M > 512) launch_one<4, 2, 1, 2, 4, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
         else launch_one<4, 1, 1, 2, 5, EPI_SILU_FRAG>(A, W, C, M, N, K, ldc, st);
-        return;
+        return false;
     }
     if (N >= 16384) {      // wide output, up to 256 rows (LM head of a small batch): one pass over K like every wide GEMM
         launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
-        return;
+        return false;
     }
     // Narrow outputs: K in slices (see gemm_kernel).  With few rows a 128x128 tile grid leaves most CUs idle and
     // every workgroup walks all of K alone (down projection: 296 k-tiles), so the slices go to separate
@@ -498,7 +498,7 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     if (slices == 1) {
         if (M > 512) launch_cfg3<2, 4, 2, 1, 4>(epi, A, W, C, M, N, K, ldc, st);
         else launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
-        return;
+        return false;
     }
     const size_t mn = (size_t)M * N;
     // few rows: slices over workgroups when the tile grid alone would not fill the chip or K is long
@@ -511,10 +511,14 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         const size_t mn4 = mn / 4;
         const dim3 g((unsigned)((mn4 + 255) / 256));
         const float4 *w4 = reinterpret_cast<const float4 *>(ws);
+        if (epi == EPI_RESID_F32 && tail) {      // the kernel that adds the partials also normalises the finished rows
+            launch_reduce_resid_rmsnorm(ws, slices, reinterpret_cast<float *>(C), tail->g, tail->y, M, N, tail->eps, st);
+            return true;
+        }
         if (epi == EPI_RESID_F32) gemm_reduce_kernel<EPI_RESID_F32><<<g, 256, 0, st>>>(w4, slices, mn4, C);
         else if (epi == EPI_BF16_ROWMAJOR) gemm_reduce_kernel<EPI_BF16_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
         else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
-        return;
+        return false;
     }
     if (M <= 512) {      // few rows, enough tiles (QKV at a few hundred rows): 128x64 tiles, slices folded in registers
         switch (epi) {
@@ -522,7 +526,7 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         case EPI_RESID_F32: launch_one<2, 2, 2, 1, 5, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
         default: launch_one<2, 2, 2, 1, 5, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
         }
-        return;
+        return false;
     }
     // Many rows: one workgroup per tile folds the slices in registers.  128x128 tiles (8 waves), or 192x128 (12 waves) when
     // that needs fewer rounds of workgroups times tile height: 1560 rows x 3584 columns are 364 tiles of 128 rows (two
@@ -543,11 +547,12 @@ void launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         case EPI_RESID_F32: launch_one<3, 4, 2, 1, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
         default: launch_one<3, 4, 2, 1, 3, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
         }
-        return;
+        return false;
     }
     switch (epi) {
     case EPI_BF16_ROWMAJOR: launch_one<2, 4, 2, 1, 4, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
     case EPI_RESID_F32: launch_one<2, 4, 2, 1, 4, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
     default: launch_one<2, 4, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
     }
+    return false;
 }

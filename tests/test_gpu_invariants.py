@@ -72,7 +72,12 @@ def test_gpu_speculative_rounds_equal_gpu_plain_decoding(shape, ctxs):
     dm.free()
 
 
-@pytest.mark.parametrize("shape", [di.MODELS["tiny"], NARROW_7B], ids=["tiny", "7b-heads"])
+# a long FFN: the down projection sums K in slices and, in passes of up to 512 rows, its slice-summing kernel also applies
+# the next RMSNorm
+LONG_FFN = di.ModelShape("longffn", 2, 256, 4, 2, 64, 8448, 2048, rope_theta=1.0e4)
+
+
+@pytest.mark.parametrize("shape", [di.MODELS["tiny"], NARROW_7B, LONG_FFN], ids=["tiny", "7b-heads", "long-ffn"])
 def test_logit_rows_do_not_depend_on_the_size_of_the_pass(shape):
     """The logits of a sequence's rows are the same bits whether it is verified alone (16 rows), in a batch of 13
     (208 rows), of 40 (640 rows) or of 70 (1120 rows): every launch-shape threshold of the row-wise kernels and of the
