@@ -3,21 +3,18 @@
 // query and the probabilities go in as ONE term each (as bf16 each needed a hi + lo pair to keep the scores and the
 // weighted sum at fp32-like accuracy, which doubled the matrix work).
 //
-// One workgroup = one (sequence, KV head, 1024-token chunk).  All G*(1+k_i)
-// query rows that share the KV head are served by ONE pass over the chunk's
-// KV: arithmetic per KV byte is G*(1+k) <= 231 flop/B, below the machine's
-// ridge, so the kernel is built around streaming pages at HBM rate:
-//   * pages are stored in MFMA operand order, so a 32-token tile (2 pages of K
-//     and of V) is four contiguous runs copied to LDS with coalesced 16-byte
-//     loads, double buffered, and read back lane-linearly (no bank conflicts);
-//   * S^T = K Q^T with v_mfma_f32_16x16x32_f16 puts 8 tokens of one query row
-//     in each lane, so the row max needs two cross-lane steps and the
-//     probabilities are already laid out as the B operand of O^T += V^T P^T;
-//   * chunks start at absolute multiples of 1024 tokens and each chunk is
-//     reduced from scratch, then chunks are merged in ascending order: a row's
-//     result does not depend on the batch it is verified in (speculative
+// One workgroup = one (sequence, KV head, chunk of pm.chunk tokens: 2048, or 1024 for models with two KV heads).
+// All G*(1+k_i) query rows that share the KV head are served by ONE pass over the chunk's KV: arithmetic per KV
+// byte is G*(1+k) <= 231 flop/B, below the machine's ridge, so the kernel is built around streaming pages at HBM rate:
+//   * pages are stored in MFMA operand order, so a 32-token tile (2 pages of K and of V) is four contiguous runs
+//     copied to LDS with coalesced 16-byte loads (asynchronous, non-temporal, a ring of four tiles that never
+//     drains) and read back lane-linearly (no bank conflicts);
+//   * S^T = K Q^T with v_mfma_f32_16x16x32_f16 puts 8 tokens of one query row in each lane, so the row max needs
+//     two cross-lane steps and the probabilities are already laid out as the B operand of O^T += V^T P^T;
+//   * chunks start at absolute multiples of the chunk length and each chunk is reduced from scratch, then chunks
+//     are merged in ascending order: a row's result does not depend on the batch it is verified in (speculative
 //     verification and one-token decoding give bit-identical rows).
-// Wave w (of 8) owns query-row blocks (16 rows each) w*RBW .. w*RBW+RBW-1.
+// Wave w (of 8, or of 16) owns query-row blocks (16 rows each) w*RBW .. w*RBW+RBW-1.
 #include "das_internal.h"
 #include <cstdlib>
 
@@ -38,7 +35,9 @@ __device__ __forceinline__ float2 unpack_h2(uint32_t u) {
 
 // 16-byte-per-lane asynchronous copy HBM -> LDS (no VGPR staging): lane l's 16 bytes land at
 // lds_wave_base + 16*l.  Inline assembly, so that the copies are ordered only by the explicit
-// s_waitcnt/s_barrier of the tile loop (M0 carries the LDS address; 1 wait state before its use).
+// s_waitcnt/s_barrier of the tile loop (M0 carries the LDS address; 1 wait state before its use).  The KV stream is
+// read once per launch: the non-temporal hint keeps it from pushing the split-KV partials, which are written here and
+// read back by the merge kernel, out of the caches (measured: attention -10 %, merge -20 %).
 __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
