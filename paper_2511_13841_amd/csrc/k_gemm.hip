@@ -36,6 +36,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // launches can spread the slices over workgroups without changing a single bit of the result:
 // 1: this workgroup walks all slices and folds each finished slice into a second set of registers;
 // 2: this workgroup computes slice blockIdx.y and stores the raw fp32 partial to slab blockIdx.y of Cv ([slices][M][ldc]).
+// PIPE: the k loop is pipelined across k-tiles and its instruction order is pinned (see k_loop_pipe).
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
@@ -443,8 +444,9 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
                  float *ws, size_t ws_floats, const GemmNormTail *tail) {
     if (M <= 0) return false;
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
-    //  * wide outputs (gate/up, LM head): 256x256, 8 waves (2 x 4) of 128x64 -- half the bytes per flop of a
-    //    128x128 tile through the HBM->LDS copy path, which is what saturates first;
+    //  * wide outputs (gate/up, LM head): 256x256 -- half the bytes per flop of a 128x128 tile through the HBM->LDS
+    //    copy path, which is what saturates first -- on 4 waves of 128x128 with the pipelined k loop at many rows,
+    //    on 8 waves (2 x 4) of 128x64 or 12 waves of 96x64 (288x256) otherwise;
     //  * narrow outputs (QKV, O, down; N of a few thousand): 128x128 with 8 waves and a 4-stage ring so that the
     //    one workgroup a CU gets covers the copy latency by itself;
     //  * few rows (T <= 512: weight streaming): 128x64 tiles, 5 stages, twice as many workgroups.
