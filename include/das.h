@@ -155,6 +155,13 @@ int das_debug_free_pages(das_model *m, int64_t *n_free);
 /* Stand-alone run of the MFMA GEMM kernel the projections use: c[M][N] (fp32) = a[M][K] * w[N][K]^T,
  * a and w row-major bf16, K a multiple of 8.  Needs no model. */
 int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c);
+/* The same kernel with its other two epilogues, on row-major bf16 host inputs a[M][K] (K a multiple of 64):
+ * act[M][F] (host, fp32 values of the bf16 the kernel stores) = silu(a wg^T) * (a wu^T) with wg, wu [F][K], F a
+ * multiple of 8 -- the gate/up projection (Sec. 3 names the model families; SwiGLU FFN);
+ * col[M] (host) = lowest column holding the row maximum of a w^T, w [N][K], N >= 16384 -- the LM head of a greedy
+ * pass, which writes no logits.  Pass F = 0 or N = 0 (and NULLs) to skip one of them.  Needs no model. */
+int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a, int32_t F, const uint16_t *wg, const uint16_t *wu,
+                             float *act, int32_t N, const uint16_t *w, int32_t *col);
 
 /* Device-to-device copy of `bytes` (multiple of 16) by a trivial kernel, `repeats` times: a dispatch of
  * known HBM traffic (bytes read + bytes written) against which profiler byte counters are scaled. */

@@ -65,6 +65,7 @@ def lib():
             "das_debug_seq": [P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I), VP, C.POINTER(I)],
             "das_debug_free_pages": [P, C.POINTER(C.c_int64)],
             "das_debug_gemm": [I, I, I, VP, VP, VP],
+            "das_debug_gemm_epilogues": [I, I, VP, I, VP, VP, VP, I, VP, VP],
             "das_debug_copy": [C.c_int64, I],
             "das_profile_enable": [P, I],
             "das_profile_reset": [P],
@@ -119,6 +120,30 @@ def debug_gemm(a_bf16, w_bf16):
     c = np.empty((M, N), np.float32)
     _chk(lib().das_debug_gemm(M, N, K, a.ctypes.data, w.ctypes.data, c.ctypes.data), "das_debug_gemm")
     return c
+
+
+def debug_gemm_silu(a_bf16, wg_bf16, wu_bf16):
+    """silu(a wg^T) * (a wu^T) through the gate/up GEMM; the kernel's bf16 result as fp32 [M][F]."""
+    a = np.ascontiguousarray(a_bf16, dtype=np.uint16)
+    wg = np.ascontiguousarray(wg_bf16, dtype=np.uint16)
+    wu = np.ascontiguousarray(wu_bf16, dtype=np.uint16)
+    M, K = a.shape
+    F = wg.shape[0]
+    out = np.empty((M, F), np.float32)
+    _chk(lib().das_debug_gemm_epilogues(M, K, a.ctypes.data, F, wg.ctypes.data, wu.ctypes.data, out.ctypes.data, 0, None, None),
+         "das_debug_gemm_epilogues")
+    return out
+
+
+def debug_gemm_rowmax(a_bf16, w_bf16):
+    """Lowest column of every row's maximum of a w^T through the LM-head GEMM that writes no logits."""
+    a = np.ascontiguousarray(a_bf16, dtype=np.uint16)
+    w = np.ascontiguousarray(w_bf16, dtype=np.uint16)
+    M, K = a.shape
+    col = np.empty(M, np.int32)
+    _chk(lib().das_debug_gemm_epilogues(M, K, a.ctypes.data, 0, None, None, None, w.shape[0], w.ctypes.data, col.ctypes.data),
+         "das_debug_gemm_epilogues")
+    return col
 
 
 def debug_copy(nbytes, repeats=1):

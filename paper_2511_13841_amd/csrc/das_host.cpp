@@ -893,6 +893,59 @@ extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a
     return rc;
 }
 
+// Stand-alone check of the GEMM's other two epilogues, from row-major bf16 host inputs:
+//   act[M][F] = silu(a wg^T) * (a wu^T), rounded to bf16 as the kernel writes it, returned as fp32 (wg, wu: [F][K]);
+//   col[M]    = lowest column of the row maximum of a w^T (w: [N][K], N >= 16384: the fused LM head).
+// Either output may be NULL with its inputs.  K % 64 == 0.
+extern "C" int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a, int32_t F, const uint16_t *wg, const uint16_t *wu,
+                                        float *act, int32_t N, const uint16_t *w, int32_t *col) {
+    const bool do_silu = F > 0 && wg && wu && act, do_max = N > 0 && w && col;
+    if (M < 1 || K < 64 || (K % 64) || !a || (!do_silu && !do_max) || (do_silu && (F % 8)) || (do_max && N < 16384)) return DAS_ERR_INVALID;
+    const int Mp = round_up(M, 256), Fp = do_silu ? round_up(F, 64) : 0, gup = round_up(2 * Fp, 256), Np = round_up(std::max(N, 1), 256);
+    bf16_t *da = nullptr, *pa = nullptr, *dw = nullptr, *pw = nullptr, *dact = nullptr;
+    unsigned long long *keys = nullptr;
+    int *dcol = nullptr;
+    int rc = DAS_OK;
+    auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
+    do {
+        if (bad(hipMalloc((void **)&da, (size_t)M * K * 2)) || bad(hipMalloc((void **)&pa, (size_t)Mp * K * 2))) break;
+        if (bad(hipMemcpy(da, a, (size_t)M * K * 2, hipMemcpyHostToDevice))) break;
+        launch_pack_weight(da, pa, M, K, Mp, K, nullptr);
+        if (do_silu) {
+            if (bad(hipMalloc((void **)&dw, (size_t)2 * F * K * 2)) || bad(hipMalloc((void **)&pw, (size_t)gup * K * 2)) ||
+                bad(hipMalloc((void **)&dact, (size_t)Mp * Fp * 2))) break;
+            if (bad(hipMemcpy(dw, wg, (size_t)F * K * 2, hipMemcpyHostToDevice)) ||
+                bad(hipMemcpy(dw + (size_t)F * K, wu, (size_t)F * K * 2, hipMemcpyHostToDevice))) break;
+            if (bad(hipMemset(pw, 0, (size_t)gup * K * 2)) || bad(hipMemset(dact, 0, (size_t)Mp * Fp * 2))) break;
+            launch_pack_gateup(dw, dw + (size_t)F * K, pw, F, K, Fp, nullptr);
+            launch_gemm(EPI_SILU_FRAG, pa, pw, dact, M, 2 * Fp, K, Fp, nullptr, nullptr, 0);
+            if (bad(hipDeviceSynchronize())) break;
+            std::vector<bf16_t> h((size_t)Mp * Fp);
+            if (bad(hipMemcpy(h.data(), dact, h.size() * 2, hipMemcpyDeviceToHost))) break;
+            for (int r = 0; r < M; ++r)
+                for (int f = 0; f < F; ++f) {
+                    const uint32_t u = (uint32_t)h[frag_off(r, f, Fp)] << 16;
+                    float v; std::memcpy(&v, &u, 4);
+                    act[(size_t)r * F + f] = v;
+                }
+            (void)hipFree(dw); (void)hipFree(pw); dw = pw = nullptr;
+        }
+        if (do_max) {
+            if (bad(hipMalloc((void **)&dw, (size_t)N * K * 2)) || bad(hipMalloc((void **)&pw, (size_t)Np * K * 2)) ||
+                bad(hipMalloc((void **)&keys, (size_t)M * 8)) || bad(hipMalloc((void **)&dcol, (size_t)M * 4))) break;
+            if (bad(hipMemcpy(dw, w, (size_t)N * K * 2, hipMemcpyHostToDevice))) break;
+            launch_pack_weight(dw, pw, N, K, Np, K, nullptr);
+            launch_rowmax_keys_clear(keys, M, nullptr);
+            launch_gemm(EPI_ROWMAX, pa, pw, keys, M, N, K, N, nullptr, nullptr, 0);
+            launch_rowmax_keys_decode(keys, M, dcol, nullptr);
+            if (bad(hipDeviceSynchronize())) break;
+            if (bad(hipMemcpy(col, dcol, (size_t)M * 4, hipMemcpyDeviceToHost))) break;
+        }
+    } while (0);
+    (void)hipFree(da); (void)hipFree(pa); (void)hipFree(dw); (void)hipFree(pw); (void)hipFree(dact); (void)hipFree(keys); (void)hipFree(dcol);
+    return rc;
+}
+
 // Plain device-to-device copy of `bytes` (multiple of 16) with a trivial kernel: the known-traffic
 // reference that scales the profiler's HBM byte counters.
 extern "C" int das_debug_copy(int64_t bytes, int32_t repeats) {

@@ -309,6 +309,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int j = 0; j < TN; j += 2) {
                 const int fbase = ((n0 + j * 32) >> 6) * 32;
+                if (fbase >= Fp) continue;      // column blocks of the last tile past the (padded) FFN width
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     bf16_t o[4];

@@ -27,6 +27,51 @@ def test_mfma_gemm_against_fp64(das, M, N, K):
     np.testing.assert_allclose(c, ref, rtol=0, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
 
 
+@pytest.mark.parametrize("M,F,K", [(7, 8200, 128), (70, 8192, 192), (200, 8256, 128), (272, 8192, 256), (330, 8448, 128),
+                                   (530, 8192, 192), (1088, 8320, 128), (40, 96, 256), (300, 160, 128), (700, 256, 192)])
+def test_gate_up_silu_epilogue_against_fp64(das, M, F, K):
+    """silu(a Wg^T) * (a Wu^T) through the gate/up GEMM (every launch shape: wide outputs at 7 ... 1088 rows, narrow ones)
+    against fp64 on the same bf16 inputs; the kernel rounds its result to bf16."""
+    rng = np.random.default_rng(M + F)
+    a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    wg = di.f32_to_bf16(rng.standard_normal((F, K)).astype(np.float32) * 0.1)
+    wu = di.f32_to_bf16(rng.standard_normal((F, K)).astype(np.float32) * 0.1)
+    print(f"gate/up M={M} F={F} K={K}", flush=True)
+    got = das.debug_gemm_silu(a, wg, wu)
+    A = di.bf16_to_f32(a).astype(np.float64)
+    g = A @ di.bf16_to_f32(wg).astype(np.float64).T
+    u = A @ di.bf16_to_f32(wu).astype(np.float64).T
+    ref = g / (1.0 + np.exp(-g)) * u
+    # bf16 rounding of the result (2^-9 relative) plus fp32 accumulation and the fast reciprocal of the sigmoid
+    np.testing.assert_allclose(got, ref, rtol=2.0 ** -8, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 16384, 128), (300, 16640, 192), (530, 16400, 128), (1088, 16384, 256)])
+def test_row_maximum_epilogue_against_fp64(das, M, N, K):
+    """The LM-head GEMM of a greedy pass keeps only the lowest column of each row's maximum: equal to the argmax of
+    the fp64 product wherever its top two values are further apart than the fp32 accumulation error; planted ties
+    (duplicated weight rows) must resolve to the lower column."""
+    rng = np.random.default_rng(M + N)
+    a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    w = di.f32_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.1)
+    # planted exact ties that are the row maximum in most rows: columns 3 and N-7 carry the same large weight row,
+    # columns 5000 and 5001 its negative
+    big = di.f32_to_bf16(rng.standard_normal(K).astype(np.float32) * 2.0)
+    w[3] = w[N - 7] = big
+    w[5000] = w[5001] = big ^ np.uint16(0x8000)
+    print(f"row max M={M} N={N} K={K}", flush=True)
+    got = das.debug_gemm_rowmax(a, w)
+    ref = di.bf16_to_f32(a).astype(np.float64) @ di.bf16_to_f32(w).astype(np.float64).T
+    want = ref.argmax(axis=1)                                  # numpy: first maximum
+    top2 = np.partition(ref, -2, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0] > 1e-4 * np.sqrt(K) * np.abs(ref).max()) | np.isin(want, [3, 5000])
+    assert clear.sum() > 0.8 * M and np.isin(want, [3, 5000]).sum() > 0.5 * M
+    np.testing.assert_array_equal(got[clear], want[clear])
+    # rows the tolerance leaves open must still name a column whose value is within it of the maximum
+    open_rows = np.nonzero(~clear)[0]
+    assert np.all(ref[open_rows, got[open_rows]] >= ref[open_rows].max(axis=1) - 1e-4 * np.sqrt(K) * np.abs(ref).max())
+
+
 @pytest.mark.parametrize("N,K", [(320, 3584), (192, 18944), (16416, 1024), (256, 960)])
 def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K):
     """A row of the product is the same bits whether it is computed among 7, 70, 300 or 600 rows: narrow outputs sum
