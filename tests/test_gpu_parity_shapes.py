@@ -81,7 +81,8 @@ def _rounds(dm, om, mirror, ids, seqs, rng, shape, budgets_per_round, rep):
 @pytest.mark.parametrize("shape,ctxs", [
     (NARROW_7B, [5, 1019, 1024, 1031, 3000, 20011, 16, 2047]),
     (NARROW_15B, [1, 777, 1008, 2048, 9000, 33]),
-], ids=["7b-heads", "1.5b-heads"])
+    (di.MODELS["tiny"], [1, 1000, 1020, 2040, 4100, 60]),          # head dim 64, chunks of 1024 tokens
+], ids=["7b-heads", "1.5b-heads", "head-dim-64"])
 def test_ragged_long_context_attention(shape, ctxs):
     dm, om, mirror, ids, seqs, rng = _setup(shape, ctxs, seed=2024)
     rep = StepReport()
