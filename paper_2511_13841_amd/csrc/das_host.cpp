@@ -354,7 +354,9 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     dm.F = c.d_ffn; dm.V = c.vocab; dm.G = dm.Hq / dm.Hkv; dm.Fp = round_up(dm.F, 64);
     dm.qkvN = (dm.Hq + 2 * dm.Hkv) * dm.D; dm.rope_theta = c.rope_theta; dm.rms_eps = c.rms_eps;
     m->max_pages = pages_for(c.max_ctx);
-    m->Mp = round_up(c.max_rows, 256);
+    // GEMM tiles may read activation rows past the last one (tile heights 64 ... 288 do not all divide 256): the row
+    // count of every activation buffer is rounded up to 256 and one more tile of slack is added
+    m->Mp = round_up(c.max_rows, 256) + 256;
     const int d = dm.d, qd = dm.Hq * dm.D, kd = dm.Hkv * dm.D, F = dm.F, Fp = dm.Fp, V = dm.V;
     const size_t Mp = m->Mp;
     int rc;
@@ -870,7 +872,7 @@ extern "C" int das_debug_free_pages(das_model *m, int64_t *n_free) {
 // Stand-alone check of the MFMA GEMM: C[M][N] = A[M][K] * W[N][K]^T from row-major bf16 host inputs.
 extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c) {
     if (M < 1 || N < 1 || K < 8 || (K % 8) || !a || !w || !c) return DAS_ERR_INVALID;
-    const int Mp = round_up(M, 256), Np = round_up(N, 256), Kp = round_up(K, 64);
+    const int Mp = round_up(M, 256) + 256, Np = round_up(N, 256), Kp = round_up(K, 64);
     bf16_t *da = nullptr, *dw = nullptr, *pa = nullptr, *pw = nullptr;
     float *dc = nullptr, *dws = nullptr;
     int rc = DAS_OK;
@@ -901,7 +903,7 @@ extern "C" int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a,
                                         float *act, int32_t N, const uint16_t *w, int32_t *col) {
     const bool do_silu = F > 0 && wg && wu && act, do_max = N > 0 && w && col;
     if (M < 1 || K < 64 || (K % 64) || !a || (!do_silu && !do_max) || (do_silu && (F % 8)) || (do_max && N < 16384)) return DAS_ERR_INVALID;
-    const int Mp = round_up(M, 256), Fp = do_silu ? round_up(F, 64) : 0, gup = round_up(2 * Fp, 256), Np = round_up(std::max(N, 1), 256);
+    const int Mp = round_up(M, 256) + 256, Fp = do_silu ? round_up(F, 64) : 0, gup = round_up(2 * Fp, 256), Np = round_up(std::max(N, 1), 256);
     bf16_t *da = nullptr, *pa = nullptr, *dw = nullptr, *pw = nullptr, *dact = nullptr;
     unsigned long long *keys = nullptr;
     int *dcol = nullptr;

@@ -438,7 +438,8 @@ static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int 
     }
 }
 
-// A must be allocated for M rounded up to 256 rows, W for N rounded up to 256 rows; K % 64 == 0.
+// A must be allocated for M rounded up to 256 rows plus another 256 (tiles of 96, 192 or 288 rows read past a multiple
+// of 256), W for N rounded up to 256 rows; K % 64 == 0.
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
