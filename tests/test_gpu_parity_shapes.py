@@ -95,6 +95,45 @@ def test_ragged_long_context_attention(shape, ctxs):
     dm.free()
 
 
+def test_needle_tokens_at_page_tile_and_chunk_edges():
+    """With random KV a single mishandled context token is diluted among thousands and hides under the logit
+    tolerance.  Here every sequence carries one needle: a KV position whose key is so large that the heads whose query
+    points its way put all their weight on it, and whose value is large.  The needles sit on the first and last token of
+    a page, of a 32-token tile, of the 1024- and 2048-token chunk boundaries, and at the end of the context.  A kernel
+    that drops, duplicates or misplaces an edge token moves the logits far beyond the tolerance."""
+    shape = NARROW_7B
+    c = 2100
+    needles = [0, 15, 16, 31, 32, 1023, 1024, 2047, 2048, c - 1, c - 16, c - 17, 2079, 2080]
+    ctxs = [c] * len(needles) + [20000, 20000]
+    needles += [19999, 4096]
+    dm, om, mirror, ids, seqs, rng = _setup(shape, ctxs, seed=77)
+    H, D = shape.n_kv_heads, shape.head_dim
+    for sid, s, p in zip(ids, seqs, needles):
+        for layer in range(shape.n_layers):
+            k = np.zeros((1, H, D), np.float32)
+            k[0, :, int(rng.integers(0, D))] = 600.0 * (1 if rng.random() < 0.5 else -1)
+            v = (rng.standard_normal((1, H, D)) * 6.0).astype(np.float32)
+            kb, vb = di.f32_to_bf16(k), di.f32_to_bf16(v)
+            dm.kv_import(sid, layer, p, kb, vb)
+            s.kv(layer, 0)[p] = di.bf16_to_f32(kb)[0]
+            s.kv(layer, 1)[p] = di.bf16_to_f32(vb)[0]
+    rep = StepReport()
+    n = len(ctxs)
+    _rounds(dm, om, mirror, ids, seqs, rng, shape, [np.array(([16, 3, 0, 8] * 4)[:n]), np.array(([1, 16, 16, 2] * 4)[:n])], rep)
+    print(rep)
+    assert rep.max_rel_logit_err < 3e-2
+    # the needles matter: without them the logits are different by far more than the tolerance
+    s0 = seqs[0]
+    before = om.verify_logits(s0, np.array([], np.int32))
+    saved = [(s0.kv(layer, 0)[needles[0]].copy(), s0.kv(layer, 1)[needles[0]].copy()) for layer in range(shape.n_layers)]
+    for layer in range(shape.n_layers):
+        s0.kv(layer, 0)[needles[0]] = 0.0
+        s0.kv(layer, 1)[needles[0]] = 0.0
+    after = om.verify_logits(s0, np.array([], np.int32))
+    assert np.abs(after - before).max() > 0.3 * np.abs(before).max()
+    dm.free()
+
+
 def test_config5_budgets_up_to_32():
     """Stochastic-config geometry: budgets 0..32 (33 rows x group 7 = 231 query rows per KV head)."""
     shape = NARROW_7B
