@@ -339,16 +339,16 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
 }
 
 // ---------------------------------------------------------------- merge of the chunk partials
-// One wave per (sequence, 16-row block, KV head, pair of dim blocks): lane l holds row l%16 and dims
+// One workgroup per (sequence, 16-row block, KV head), one wave per pair of dim blocks: lane l holds row l%16 and dims
 // 16*db + 4*(l/16) .. +3 of its two dim blocks, as the attention kernel left them.  A chunk contributes its
 // normalised output with weight l * 2^(m - M); ascending chunk order, fp32; chunks a row cannot see carry
 // m = -inf and are skipped.  Output: bf16, fragment order, K = Hq*D.
 template <int D>
-__global__ __launch_bounds__(64) void attn_merge_kernel(PassMeta pm, const uint16_t *__restrict__ part_o,
+__global__ __launch_bounds__(64 * (D / 32)) void attn_merge_kernel(PassMeta pm, const uint16_t *__restrict__ part_o,
                                                         const float *__restrict__ part_ml, bf16_t *__restrict__ out,
                                                         int Hq, int Hkv, int G) {
     const int b = pm.mblk[2 * blockIdx.x], rb = pm.mblk[2 * blockIdx.x + 1];
-    const int kvh = blockIdx.y, q = blockIdx.z, lane = threadIdx.x;     // this wave: dim blocks 2q and 2q+1
+    const int kvh = blockIdx.y, q = threadIdx.y, lane = threadIdx.x;     // this wave: dim blocks 2q and 2q+1
     const int n = pm.b_n[b];
     const int R = G * n, nrb = (R + 15) >> 4, nchunk = pm.b_nchunk[b];
     const int rr = rb * 16 + (lane & 15);
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(PassMeta pm, const uint1
 void launch_attn_merge(const PassMeta &pm, const uint16_t *part_o, const float *part_ml, bf16_t *out_frag,
                        const DasDims &dm, hipStream_t st) {
     if (pm.n_mblk <= 0) return;
-    dim3 g(pm.n_mblk, dm.Hkv, dm.D / 32), blk(64);
+    dim3 g(pm.n_mblk, dm.Hkv), blk(64, dm.D / 32);      // one wave per pair of dim blocks
     if (dm.D == 128) attn_merge_kernel<128><<<g, blk, 0, st>>>(pm, part_o, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
     else attn_merge_kernel<64><<<g, blk, 0, st>>>(pm, part_o, part_ml, out_frag, dm.Hq, dm.Hkv, dm.G);
 }
