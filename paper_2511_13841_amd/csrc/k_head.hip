@@ -97,10 +97,20 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(const float *__restrict
     }
 }
 
-// One workgroup per sequence.  Rows j = 0..k-1: accept draft j+1 iff u_accept*Z < w(draft).
-// Then an inverse-CDF draw (ascending vocabulary order) from the row where the walk stopped,
-// with the rejected draft's weight removed.  Thread t owns the contiguous slice
-// [t*seg, (t+1)*seg) so that the cumulative sum runs in index order.
+// One workgroup (16 waves) per sequence.  Rows j = 0..k-1: accept draft j+1 iff u_accept*Z < w(draft); the rows are tested
+// side by side, one per lane, and the first rejection is taken from a ballot.  Then an inverse-CDF draw (ascending
+// vocabulary order) from the row where the walk stopped, with the rejected draft's weight removed: wave w owns the
+// contiguous segment [w*seg, (w+1)*seg) and walks it 64 consecutive columns at a time (coalesced), keeping the running
+// sum of an inclusive scan over the lanes, so that the cumulative sum runs in index order; the 16 segment totals are
+// added in order, and the wave whose segment holds the crossing walks it a second time to name the column.
+__device__ __forceinline__ float wave_inclusive_scan(float v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float t = __shfl_up(v, o);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
 __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__restrict__ logits, int V,
                                                              const int *__restrict__ tok, const int *__restrict__ b_row0,
                                                              const int *__restrict__ b_n, float inv_temp,
@@ -108,69 +118,96 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__rest
                                                              const float *__restrict__ u_sample, int prefill_mode,
                                                              const float *__restrict__ stats, int *__restrict__ accept_len,
                                                              int *__restrict__ next_token) {
-    __shared__ float part[1024];
-    __shared__ int lastnz[16];
-    __shared__ int result;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    __shared__ float seg_total[16];
+    __shared__ int seg_lastnz[16];
+    __shared__ int walk[2];          // accepted drafts, rejected token
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = prefill_mode ? b : b_row0[b];
     const int k = prefill_mode ? 0 : b_n[b] - 1;
-    int a = 0, rejected = -1;
-    for (; a < k; ++a) {
-        const int r = r0 + a, d = tok[r + 1];
-        const float mx = stats[2 * r], Z = stats[2 * r + 1];
-        const float wd = __expf((logits[(size_t)r * V + d] - mx) * inv_temp);
-        if (!(u_accept[r] * Z < wd)) { rejected = d; break; }
+    if (wave == 0) {
+        int a = k, rejected = -1;
+        for (int base = 0; base < k && a == k; base += 64) {
+            const int jrow = base + lane;
+            bool rej = false;
+            int d = -1;
+            if (jrow < k) {
+                const int r = r0 + jrow;
+                d = tok[r + 1];
+                const float mx = stats[2 * r], Z = stats[2 * r + 1];
+                const float wd = __expf((logits[(size_t)r * V + d] - mx) * inv_temp);
+                rej = !(u_accept[r] * Z < wd);
+            }
+            const unsigned long long m = __ballot(rej);
+            if (m) {
+                const int first = __ffsll((long long)m) - 1;
+                a = base + first;
+                rejected = __shfl(d, first);
+            }
+        }
+        if (lane == 0) { walk[0] = a; walk[1] = rejected; }
     }
+    __syncthreads();
+    const int a = walk[0], rejected = walk[1];
     const int r = r0 + a;
     const float *x = logits + (size_t)r * V;
     const float mx = stats[2 * r];
     const float u = prefill_mode ? u_sample[b] : u_sample[r];
-    const int seg = (V + 1023) / 1024;
-    const int lo = tid * seg, hi = min(lo + seg, V);
-    float s = 0.f;
+    const int seg = (((V + 15) / 16) + 63) & ~63;          // columns per wave, a multiple of 64
+    const int lo = wave * seg, hi = min(lo + seg, V);
+    auto weight = [&](int i) { return (i < hi && i != rejected) ? __expf((x[i] - mx) * inv_temp) : 0.f; };
+    float run = 0.f;
     int nz = -1;
-    for (int i = lo; i < hi; ++i) {
-        const float w = (i == rejected) ? 0.f : __expf((x[i] - mx) * inv_temp);
-        s += w;
-        if (w > 0.f) nz = i;
+    for (int base = lo; base < hi; base += 256) {          // four loads in flight per lane; the sums stay in index order
+        float w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w[q] = weight(base + 64 * q + lane);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (w[q] > 0.f) nz = base + 64 * q + lane;
+            run += __shfl(wave_inclusive_scan(w[q], lane), 63);
+        }
     }
-    part[tid] = s;
-    const int nz_local = nz;
     for (int o = 32; o > 0; o >>= 1) nz = max(nz, __shfl_xor(nz, o));
-    if ((tid & 63) == 0) lastnz[tid >> 6] = nz;
-    if (tid == 0) result = -1;
+    if (lane == 0) { seg_total[wave] = run; seg_lastnz[wave] = nz; }
     __syncthreads();
-    // inclusive scan of the 1024 slice sums (Hillis-Steele; fixed order)
-    for (int o = 1; o < 1024; o <<= 1) {
-        float v = (tid >= o) ? part[tid - o] : 0.f;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
+    float before = 0.f, total = 0.f;
+    int owner = -1;
+    {
+        float c = 0.f;
+        for (int w = 0; w < 16; ++w) {
+            if (w == wave) before = c;
+            c += seg_total[w];
+        }
+        total = c;
+        const float target = u * total;
+        c = 0.f;
+        for (int w = 0; w < 16; ++w) {
+            c += seg_total[w];
+            if (owner < 0 && c > target) owner = w;
+        }
     }
-    const float total = part[1023];
     const float target = u * total;
-    const float excl = (tid == 0) ? 0.f : part[tid - 1];
-    if (excl <= target && part[tid] > target && lo < hi) {
-        // the crossing is inside this slice (slices with equal prefix are empty of weight)
-        float c = excl;
+    if (wave == (owner < 0 ? 0 : owner)) {
         int pick = -1;
-        for (int i = lo; i < hi; ++i) {
-            const float w = (i == rejected) ? 0.f : __expf((x[i] - mx) * inv_temp);
-            c += w;
-            if (c > target) { pick = i; break; }
+        if (owner >= 0) {
+            float c = before;
+            for (int base = lo; base < hi && pick < 0; base += 64) {
+                const float sc = wave_inclusive_scan(weight(base + lane), lane);
+                const unsigned long long m = __ballot(c + sc > target);
+                if (m) pick = base + __ffsll((long long)m) - 1;
+                c += __shfl(sc, 63);
+            }
+            // the running sum starts at the segments before this one here and at zero in the first walk: if that rounds
+            // the last step below the target, the crossing is the segment's last non-zero weight
+            if (pick < 0) pick = seg_lastnz[wave];
         }
-        if (pick < 0) pick = nz_local;        // slice total rounded differently inside the scan
-        if (pick >= 0) atomicMax(&result, pick);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int pick = result;
-        if (pick < 0) {                       // rounding pushed the target past the total: last non-zero weight
-            pick = lastnz[0];
-            for (int w = 1; w < 16; ++w) pick = max(pick, lastnz[w]);
+        if (pick < 0) {                                  // rounding pushed the target past the total: last non-zero weight
+            for (int w = 0; w < 16; ++w) pick = max(pick, seg_lastnz[w]);
         }
-        accept_len[b] = a;
-        next_token[b] = pick;
+        if (lane == 0) {
+            accept_len[b] = a;
+            next_token[b] = pick;
+        }
     }
 }
 
