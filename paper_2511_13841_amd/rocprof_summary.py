@@ -2,7 +2,7 @@
 run writes) as a short text table: per kernel calls, average and total duration, and, when the run
 collected counters, the per-dispatch average of each.
 
-    python -m paper_2511_13841_amd.rocprof_summary gpurun_out/prof/run_results.db [--top 16]
+    python -m paper_2511_13841_amd.rocprof_summary <output dir>/run_results.db [--top 16]
 """
 import argparse
 import sqlite3
