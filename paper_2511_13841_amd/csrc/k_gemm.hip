@@ -111,7 +111,16 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     // synchronises, but finishes early and frees its CU, which is worth ~10% when M is just past a multiple of
     // the tile height (T = 1088 = 4 x 256 + 64).  Straight-line variants only: per-block branches inside the
     // k loop make the compiler spill accumulators.
-    const int vb = min(TM, max(0, (M - (tile_m * AB + wm * TM) * 32 + 31) >> 5));
+    // A short last M tile (at most four of its eight row blocks hold rows) of the 2 x 2 wave layout is split by COLUMNS
+    // instead: every wave takes all valid row blocks and two of the eight column blocks, so that the four waves share
+    // the work instead of two of them doing all of it (half the time for such a tile).
+    constexpr bool CAN_COLSPLIT = PIPE && WGM == 2 && WGN == 2 && TM == 4 && TN == 4;
+    const int tile_vb = min(AB, max(0, (M - tile_m * AB * 32 + 31) >> 5));      // row blocks of this tile that hold rows
+    const bool colsplit = CAN_COLSPLIT && tile_vb <= 4;
+    const int rb0 = colsplit ? 0 : wm * TM;              // first row block and column block of this wave inside the tile
+    const int cb0 = colsplit ? wave * 2 : wn * TN;
+    const int tnv = colsplit ? 2 : TN;                   // column blocks this wave owns
+    const int vb = min(TM, max(0, (M - (tile_m * AB + rb0) * 32 + 31) >> 5));
     auto compute = [&](auto tm_tag, const unsigned char *cur, int next_kt, int next_stage) {
         constexpr int TMV = decltype(tm_tag)::value;      // row blocks 0 .. TMV-1 are multiplied
         // fragments of k-step ks+1 are requested before the MFMAs of k-step ks are issued
@@ -195,15 +204,15 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     // copy of tile kt+NS-1 starts after that barrier (every wave has left tile kt-1) and its remaining slices follow
     // in the first k-steps of tile kt+1; all of them are issued before the next such barrier, so "tile kt+1 has
     // landed" is again one constant s_waitcnt: at most NS-3 newer tiles outstanding.
-    auto k_loop_pipe = [&](auto tm_tag) {
-        constexpr int TMV = decltype(tm_tag)::value;
+    auto k_loop_pipe = [&](auto tm_tag, auto tn_tag) {
+        constexpr int TMV = decltype(tm_tag)::value, TNV = decltype(tn_tag)::value;      // row and column blocks multiplied
         static_assert(!PIPE || (NS >= 3 && SPREAD && KS % 2 == 0), "pipelined k loop: three stages, spread copies, even k-steps");
-        constexpr int NMF = TMV * TN, NRD = TMV > 0 ? TMV + TN : 0;      // MFMAs and fragment reads per k-step
-        bf16x8 a[2][TMV > 0 ? TMV : 1], b[2][TN];
+        constexpr int NMF = TMV * TNV, NRD = TMV > 0 ? TMV + TNV : 0;      // MFMAs and fragment reads per k-step
+        bf16x8 a[2][TMV > 0 ? TMV : 1], b[2][TNV];
         auto fetch_one = [&](const unsigned char *cur, int ks, int buf, int r) {      // r-th fragment of a k-step
             // weight fragments first: the MFMAs run over them in the inner loop, so both are needed by the second MFMA
-            if (r < TN) b[buf][r] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((wn * TN + r) * KS + ks) * 1024 + lane * 16);
-            else a[buf][r - TN] = *reinterpret_cast<const bf16x8 *>(cur + ((wm * TM + r - TN) * KS + ks) * 1024 + lane * 16);
+            if (r < TNV) b[buf][r] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((cb0 + r) * KS + ks) * 1024 + lane * 16);
+            else a[buf][r - TNV] = *reinterpret_cast<const bf16x8 *>(cur + ((rb0 + r - TNV) * KS + ks) * 1024 + lane * 16);
         };
         auto copy_one = [&](int kt, int stg, int j) {
             dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
@@ -251,12 +260,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
                 for (int i = 0; i < TMV; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
+                    for (int j = 0; j < TNV; ++j) {
                         if (EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
                         else
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
-                        const int slot = i * TN + j;
+                        const int slot = i * TNV + j;
                         if (requests) {
                             if (slot < NRD) fetch_one(fsrc, fks, fbuf, slot);
                             if (NRD > NMF && slot == NMF - 1) {
@@ -286,9 +295,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
         }
     };
     if (PIPE) {
-        if (vb == 0) k_loop_pipe(std::integral_constant<int, 0>{});
-        else if (TM == 4 && vb <= 2) k_loop_pipe(std::integral_constant<int, (TM == 4 ? 2 : TM)>{});
-        else k_loop_pipe(std::integral_constant<int, TM>{});
+        using TNfull = std::integral_constant<int, TN>;
+        using TNhalf = std::integral_constant<int, (CAN_COLSPLIT ? 2 : TN)>;
+        if (vb == 0) k_loop_pipe(std::integral_constant<int, 0>{}, TNfull{});
+        else if (colsplit && vb <= 2) k_loop_pipe(std::integral_constant<int, (TM == 4 ? 2 : TM)>{}, TNhalf{});
+        else if (colsplit) k_loop_pipe(std::integral_constant<int, TM>{}, TNhalf{});
+        else if (TM == 4 && vb <= 2) k_loop_pipe(std::integral_constant<int, (TM == 4 ? 2 : TM)>{}, TNfull{});
+        else k_loop_pipe(std::integral_constant<int, TM>{}, TNfull{});
     } else {
         if (vb == 0) k_loop(std::integral_constant<int, 0>{});
         else if (TM == 4 && vb <= 2) k_loop(std::integral_constant<int, (TM == 4 ? 2 : TM)>{});
@@ -296,7 +309,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     }
     __builtin_amdgcn_s_waitcnt(0xF70);     // vmcnt(0): no copy may land in LDS after this workgroup is gone
 
-    const int m0 = tile_m * AB * 32 + wm * TM * 32, n0 = tile_n * BB * 32 + wn * TN * 32;
+    const int m0 = tile_m * AB * 32 + rb0 * 32, n0 = tile_n * BB * 32 + cb0 * 32;
     const int lr = lane & 31, lh = lane >> 5;
     if (EPI == EPI_SILU_FRAG) {
         // packed weight rows come in groups of 64: 32 gate rows then the 32 up rows of the same features
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int j = 0; j < TN; j += 2) {
                 const int fbase = ((n0 + j * 32) >> 6) * 32;
-                if (fbase >= Fp) continue;      // column blocks of the last tile past the (padded) FFN width
+                if (fbase >= Fp || j >= tnv) continue;      // column blocks of the last tile past the (padded) FFN width; blocks of other waves
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     bf16_t o[4];
@@ -339,7 +352,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                 for (int r = 0; r < 16; ++r) {
                     const int col = n0 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                     const float v = acc[i][j][r] + 0.f;      // -0 -> +0: equal values must give equal keys
-                    if (col < N && v > best) { best = v; bi = col; }
+                    if (col < N && j < tnv && v > best) { best = v; bi = col; }
                 }
             uint32_t u = __float_as_uint(best);
             u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
@@ -354,7 +367,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int col = n0 + j * 32 + lr;
-                if (col >= N) continue;
+                if (col >= N || j >= tnv) continue;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
