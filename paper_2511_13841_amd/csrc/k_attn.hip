@@ -46,7 +46,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
 // without copies out of the accumulation register file on every tile.
 // DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 6 arithmetic only (no copies after
-// the first two tiles), 7 copies only and no partial stores.
+// the first two tiles), 7 copies only and no partial stores, 8 copies and LDS fragment reads without arithmetic.
 template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const f16_t *__restrict__ q_h,
@@ -147,6 +147,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         for (int ks = 0; ks < KFR; ++ks) {
             const f16x8 k0 = *reinterpret_cast<const f16x8 *>(cur + (ks * 64 + lane) * 16);
             const f16x8 k1 = *reinterpret_cast<const f16x8 *>(cur + PAGE_B + (ks * 64 + lane) * 16);
+            if (DBG == 8) { asm volatile("" ::"v"(k0), "v"(k1)); continue; }      // fragment reads without arithmetic
 #pragma unroll
             for (int i = 0; i < RBW; ++i) {
                 s.v[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0, qf[i][ks], s.v[i][0], 0, 0, 0);
@@ -227,6 +228,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
             typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
             u32x4 vv = {lo[0], lo[1], hi[0], hi[1]};
             const f16x8 vf = *reinterpret_cast<f16x8 *>(&vv);
+            if (DBG == 8) { asm volatile("" ::"v"(vf)); continue; }
 #pragma unroll
             for (int i = 0; i < RBW; ++i) acc[i][db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, p.v[i], acc[i][db], 0, 0, 0);
         }
@@ -255,8 +257,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
                 Scores s0;
                 Probs p0;
                 qk(c0, s0);
-                row_check(ti, s0);
-                probs(s0, p0);
+                if (DBG != 8) {
+                    row_check(ti, s0);
+                    probs(s0, p0);
+                }
                 pv(c0, p0);
             }
             stage = stage == NS - 1 ? 0 : stage + 1;
@@ -270,6 +274,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     // contiguous KiB per instruction.  HBM writes cost this kernel about three times their bytes in read
     // bandwidth, hence the narrow format.
     const int nrb = (R + 15) >> 4;
+    // Partials of a long sequence (many chunks) leave with non-temporal stores: they are many, the merge reads each once,
+    // and kept in the caches they cost the KV stream more than the merge gains (contexts of 32k-64k: attention -20 us,
+    // merge +7 us per layer); the few partials of short sequences stay cached for the merge.
+    const bool stream_out = pm.b_nchunk[b] >= 8;
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
         float l = l_run[i];
@@ -284,7 +292,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
 #pragma unroll
             for (int q = 0; q < VDB / 2; ++q) {
                 const f32x4 lo = acc[i][2 * q] * inv, hi = acc[i][2 * q + 1] * inv;
-                dst[q * 64] = make_uint4(pack_h2(lo[0], lo[1]), pack_h2(lo[2], lo[3]), pack_h2(hi[0], hi[1]), pack_h2(hi[2], hi[3]));
+                typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+                const u32x4 val = {pack_h2(lo[0], lo[1]), pack_h2(lo[2], lo[3]), pack_h2(hi[0], hi[1]), pack_h2(hi[2], hi[3])};
+                // (inline assembly: written with the builtin, the two branches are merged into one plain store.  The wait
+                // states cover the hazard between a 16-byte store and a later write of its data registers, which the
+                // compiler handles for its own stores only.)
+                if (stream_out) asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 4" ::"v"(dst + q * 64), "v"(val) : "memory");
+                else *reinterpret_cast<u32x4 *>(dst + q * 64) = val;
             }
         }
     }
@@ -324,6 +338,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
         case 11: launch_attn_cfg<128, 1, 1>(ATTN_ARGS); return; case 12: launch_attn_cfg<128, 2, 1>(ATTN_ARGS); return;
         case 61: launch_attn_cfg<128, 1, 6>(ATTN_ARGS); return; case 62: launch_attn_cfg<128, 2, 6>(ATTN_ARGS); return;
         case 71: launch_attn_cfg<128, 1, 7>(ATTN_ARGS); return; case 72: launch_attn_cfg<128, 2, 7>(ATTN_ARGS); return;
+        case 81: launch_attn_cfg<128, 1, 8>(ATTN_ARGS); return; case 82: launch_attn_cfg<128, 2, 8>(ATTN_ARGS); return;
         }
     }
 #endif
@@ -362,22 +377,32 @@ __global__ __launch_bounds__(64 * (D / 32)) void attn_merge_kernel(PassMeta pm, 
         ml = *reinterpret_cast<const float2 *>(part_ml + id * 32 + 2 * (lane & 15));
         v = (reinterpret_cast<const uint4 *>(part_o + id * (16 * D)) + q * 64)[lane];
     };
-    float2 ml_n;
-    uint4 v_n;
-    load(0, ml_n, v_n);
-    for (int c = 0; c < nchunk; ++c) {
-        const float2 ml = ml_n;
-        const uint4 v = v_n;
-        if (c + 1 < nchunk) load(c + 1, ml_n, v_n);        // next chunk's loads fly while this one is merged
-        if (ml.x == -INFINITY) continue;
-        const float mn = fmaxf(M, ml.x);
-        const float a0 = exp2f(M - mn), a1 = ml.y * exp2f(ml.x - mn);
-        den = den * a0 + a1;
-        const float2 o0 = unpack_h2(v.x), o1 = unpack_h2(v.y), o2 = unpack_h2(v.z), o3 = unpack_h2(v.w);
-        const float o[8] = {o0.x, o0.y, o1.x, o1.y, o2.x, o2.y, o3.x, o3.y};
+    // Four chunks in flight: the merge of a long sequence is one dependent chain of loads, and its partials come from
+    // HBM (they were written past the caches), so the depth of this ring is what its duration follows.
+    constexpr int PF = 4;
+    float2 ml_q[PF];
+    uint4 v_q[PF];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) num[e] = num[e] * a0 + o[e] * a1;
-        M = mn;
+    for (int u = 0; u < PF; ++u)
+        if (u < nchunk) load(u, ml_q[u], v_q[u]);
+    for (int c0 = 0; c0 < nchunk; c0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int c = c0 + u;
+            if (c >= nchunk) break;
+            const float2 ml = ml_q[u];
+            const uint4 v = v_q[u];
+            if (c + PF < nchunk) load(c + PF, ml_q[u], v_q[u]);
+            if (ml.x == -INFINITY) continue;
+            const float mn = fmaxf(M, ml.x);
+            const float a0 = exp2f(M - mn), a1 = ml.y * exp2f(ml.x - mn);
+            den = den * a0 + a1;
+            const float2 o0 = unpack_h2(v.x), o1 = unpack_h2(v.y), o2 = unpack_h2(v.z), o3 = unpack_h2(v.w);
+            const float o[8] = {o0.x, o0.y, o1.x, o1.y, o2.x, o2.y, o3.x, o3.y};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) num[e] = num[e] * a0 + o[e] * a1;
+            M = mn;
+        }
     }
     if (rr >= R) return;
     const int j = rr / G, g = rr % G;
