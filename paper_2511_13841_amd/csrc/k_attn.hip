@@ -296,7 +296,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
                 const u32x4 val = {pack_h2(lo[0], lo[1]), pack_h2(lo[2], lo[3]), pack_h2(hi[0], hi[1]), pack_h2(hi[2], hi[3])};
                 // (inline assembly: written with the builtin, the two branches are merged into one plain store.  The wait
                 // states cover the hazard between a 16-byte store and a later write of its data registers, which the
-                // compiler handles for its own stores only.)
+                // compiler handles for its own stores only.  No load may follow these stores in this kernel: the compiler's
+                // s_waitcnt bookkeeping does not count them.)
                 if (stream_out) asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 4" ::"v"(dst + q * 64), "v"(val) : "memory");
                 else *reinterpret_cast<u32x4 *>(dst + q * 64) = val;
             }
