@@ -451,6 +451,18 @@ static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int 
     }
 }
 
+// Compute units of the current device (asked once; 256 if the query fails).
+static int cu_count() {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        (void)hipGetLastError();
+        n_cu = cus;
+    }
+    return n_cu;
+}
+
 // A must be allocated for M rounded up to 256 rows plus another 256 (tiles of 96, 192 or 288 rows read past a multiple
 // of 256), W for N rounded up to 256 rows; K % 64 == 0.
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
@@ -474,7 +486,15 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         if (M <= 64) launch_one<2, 2, 1, 2, 6, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
         // 193..320 rows: 96x256 tiles on 4 waves of 96x64 (6 MFMAs per 5 fragment reads against 2 per 3), pipelined k loop,
         // seven stages of 22 KiB (six tiles in flight per CU): 121 -> 106 us per layer at T = 272
-        else if (M > 192) launch_one<1, 4, 3, 2, 7, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        else if (M > 192) {
+            // ... or 128x256 tiles (4 waves of 128x64) where those finish in fewer rounds of workgroups times tile height:
+            // 320 rows x 17920 packed columns are 280 tiles of 96 rows (a second round for 24 of them on 256 CUs) but 210
+            // tiles of 128 rows.  The K order per output element is the same in both.
+            const long nt = (N + 255) / 256, cus = cu_count();
+            const long cost96 = ((M + 95) / 96 * nt + cus - 1) / cus * 96, cost128 = ((M + 127) / 128 * nt + cus - 1) / cus * 128;
+            if (cost128 < cost96) launch_one<1, 4, 4, 2, 6, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else launch_one<1, 4, 3, 2, 7, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        }
         else launch_one<3, 2, 1, 2, 5, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
         return false;
     }
@@ -548,13 +568,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     // Many rows: one workgroup per tile folds the slices in registers.  128x128 tiles (8 waves), or 192x128 (12 waves) when
     // that needs fewer rounds of workgroups times tile height: 1560 rows x 3584 columns are 364 tiles of 128 rows (two
     // rounds on 256 CUs) but 252 tiles of 192 rows (one round).
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-        (void)hipGetLastError();
-        n_cu = cus;
-    }
+    const int n_cu = cu_count();
     const int tn = (N + 127) / 128;
     const long cost128 = (long)((((M + 127) / 128) * tn + n_cu - 1) / n_cu) * 128;
     const long cost192 = (long)((((M + 191) / 192) * tn + n_cu - 1) / n_cu) * 192;

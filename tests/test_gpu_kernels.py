@@ -27,10 +27,10 @@ def test_mfma_gemm_against_fp64(das, M, N, K):
     np.testing.assert_allclose(c, ref, rtol=0, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
 
 
-@pytest.mark.parametrize("M,F,K", [(7, 8200, 128), (70, 8192, 192), (200, 8256, 128), (272, 8192, 256), (330, 8448, 128),
+@pytest.mark.parametrize("M,F,K", [(7, 8200, 128), (70, 8192, 192), (200, 8256, 128), (272, 8192, 256), (320, 8960, 128), (301, 8960, 192), (330, 8448, 128),
                                    (530, 8192, 192), (1088, 8320, 128), (40, 96, 256), (300, 160, 128), (700, 256, 192)])
 def test_gate_up_silu_epilogue_against_fp64(das, M, F, K):
-    """silu(a Wg^T) * (a Wu^T) through the gate/up GEMM (every launch shape: wide outputs at 7 ... 1088 rows, narrow ones)
+    """silu(a Wg^T) * (a Wu^T) through the gate/up GEMM (every launch shape: wide outputs at 7 ... 1088 rows -- both tile heights of the 193..320-row range --, narrow ones)
     against fp64 on the same bf16 inputs; the kernel rounds its result to bf16."""
     rng = np.random.default_rng(M + F)
     a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
