@@ -264,8 +264,10 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         const LayerW &w = m->layers[l];
         f16_t *kl = m->kpool + (size_t)l * m->layer_elems, *vl = m->vpool + (size_t)l * m->layer_elems;
         if (!xn_ready) { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
-        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats); }
-        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, m->qkv, m->q_h, m->cs, kl, vl, dm, st); }
+        // (few rows: the K-slice partials of QKV stay in the workspace and the rotation kernel adds them)
+        int qkv_slices = 1;
+        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats, nullptr, &qkv_slices); }
+        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, qkv_slices > 1 ? m->gemm_ws : m->qkv, qkv_slices, m->q_h, m->cs, kl, vl, dm, st); }
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)

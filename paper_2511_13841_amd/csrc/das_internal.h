@@ -100,12 +100,17 @@ void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, in
 // qkv: fp32 [T][qkvN] projections; q is rotated and rounded to binary16 ([T][Hq*D]); k is rotated, rounded once to
 // bf16 and scattered into its page; v is rounded once to bf16 and scattered.  The pages keep those bf16 values in
 // binary16 containers (exact for 2^-17 <= |x| <= 65504; larger magnitudes saturate).
-void launch_rope_kv(const PassMeta &pm, const float *qkv, f16_t *q_h, const float *cs,
+// slices > 1: qkv points at `slices` slabs of [T][qkvN] partial sums (see launch_gemm's left_slices); the kernel adds them
+// in ascending order first, which gives the bits the GEMM's own reduce kernel would have written.
+void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h, const float *cs,
                     f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st);
 // C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
 // ws: fp32 workspace of ws_floats elements for the slice partials of narrow few-row GEMMs (may be null: slower, same result)
+// left_slices (EPI_F32_ROWMAJOR only): a caller whose next kernel can add the K-slice partials itself passes a pointer.
+// When the launch leaves the partials in ws ([slices][M][N], to be added in ascending order) it stores their count there
+// and C stays unwritten; otherwise it stores 1 and C holds the product.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr);
+                 float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr);
 int gemm_slices(int K, int *slice_tiles);
 // split-KV partial attention for the items of one row-block class, then the merge
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,

@@ -222,13 +222,14 @@ __device__ __forceinline__ f16_t kv_elem(float x) { return f2h(bf2f(f2bf(x))); }
 // grid (T, heads / heads per workgroup), block 256 = 256 / (D/2) heads: thread i of a head owns the rotate-half pair
 // (i, i + D/2).  The projections arrive in fp32 and are rounded exactly once, after the rotation: q to binary16, k and
 // v to bf16.
-__global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, f16_t *__restrict__ q_h,
+__global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, int slices, size_t slab, f16_t *__restrict__ q_h,
                                const float2 *__restrict__ cs, f16_t *__restrict__ kpool, f16_t *__restrict__ vpool,
                                int Hq, int Hkv, int D, int qkvN) {
     const int half = D >> 1, r = blockIdx.x, hh = blockIdx.y * (256 / half) + threadIdx.x / half, i = threadIdx.x % half;
     if (hh >= Hq + 2 * Hkv) return;
     const float *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
     float x1 = row[i], x2 = row[i + half];
+    for (int s = 1; s < slices; ++s) { x1 += row[s * slab + i]; x2 += row[s * slab + i + half]; }      // K-slice partials, in order
     if (hh < Hq + Hkv) {
         float2 c = cs[r * half + i];
         float y1 = x1 * c.x - x2 * c.y, y2 = x2 * c.x + x1 * c.y;
@@ -252,11 +253,11 @@ __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, f16_t
         blk[vpage_off(t, i + half)] = kv_elem(x2);
     }
 }
-void launch_rope_kv(const PassMeta &pm, const float *qkv, f16_t *q_h, const float *cs,
+void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h, const float *cs,
                     f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st) {
     const int heads_per_wg = 256 / (dm.D / 2);
     rope_kv_kernel<<<dim3(pm.T, (dm.Hq + 2 * dm.Hkv + heads_per_wg - 1) / heads_per_wg), dim3(256), 0, st>>>(
-        pm, qkv, q_h, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
+        pm, qkv, slices, (size_t)pm.T * dm.qkvN, q_h, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
 }
 
 // ---------------------------------------------------------------- KV import / export / synthetic fill

@@ -468,7 +468,8 @@ static int cu_count() {
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats, const GemmNormTail *tail) {
+                 float *ws, size_t ws_floats, const GemmNormTail *tail, int *left_slices) {
+    if (left_slices) *left_slices = 1;
     if (M <= 0) return false;
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
     //  * wide outputs (gate/up, LM head): 256x256 -- half the bytes per flop of a 128x128 tile through the HBM->LDS
@@ -552,6 +553,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             launch_reduce_resid_rmsnorm(ws, slices, reinterpret_cast<float *>(C), tail->g, tail->y, M, N, tail->eps, st);
             return true;
         }
+        if (epi == EPI_F32_ROWMAJOR && left_slices) { *left_slices = slices; return false; }      // the caller's next kernel adds them
         if (epi == EPI_RESID_F32) gemm_reduce_kernel<EPI_RESID_F32><<<g, 256, 0, st>>>(w4, slices, mn4, C);
         else if (epi == EPI_BF16_ROWMAJOR) gemm_reduce_kernel<EPI_BF16_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
         else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
