@@ -503,13 +503,18 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // 256-row or 288-row tiles (12 waves, 3 x 4), whichever pads M less: T = 1088 is 4 x 288 - 64 but 5 x 256 - 192
         const int pad256 = (M + 255) / 256 * 256, pad288 = (M + 287) / 288 * 288;
         // LM head at many rows: the same 4-wave pipelined kernel (1.10 -> 1.00 ms at T = 1088 against 288x256 tiles of 12 waves)
-        if (epi == EPI_ROWMAX && M > 512) launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        // ... and at 257..512 rows on 4 waves of 128x64 or 96x64 (128x256 or 96x256 tiles), whichever pads M less:
+        // 221 -> 186 us for the 1.5B head at 320 rows against 256x256 tiles of 8 waves
+        const bool rows96 = (M + 95) / 96 * 96 < (M + 127) / 128 * 128;
+        if (M <= 512 && pad288 >= pad256 && (epi == EPI_ROWMAX || epi == EPI_F32_ROWMAJOR)) {      // (up to 288 rows: one 288-row tile, below)
+            if (epi == EPI_ROWMAX && rows96) launch_one<1, 4, 3, 2, 7, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (epi == EPI_ROWMAX) launch_one<1, 4, 4, 2, 6, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (rows96) launch_one<1, 4, 3, 2, 7, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else launch_one<1, 4, 4, 2, 6, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        }
+        else if (epi == EPI_ROWMAX && M > 512) launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else if (epi == EPI_F32_ROWMAJOR && M > 512) launch_one<2, 2, 4, 4, 4, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
-        else if (M <= 512 && epi == EPI_F32_ROWMAJOR)      // few rows (LM head at T ~ 300): spread the copies over the k-steps
-            launch_one<2, 4, 4, 2, 2, EPI_F32_ROWMAJOR, 4, true>(A, W, C, M, N, K, ldc, st);
-        else if (M <= 512 && epi == EPI_ROWMAX)
-            launch_one<2, 4, 4, 2, 2, EPI_ROWMAX, 4, true>(A, W, C, M, N, K, ldc, st);
         else if (epi == EPI_SILU_FRAG)
             // gate/up at many rows: 4 waves (2 x 2), one per SIMD, each 128x128 of the 256x256 tile (all 256 accumulator
             // registers of the wave): 8 fragment reads per 16 MFMAs, a third less LDS traffic per MFMA than 8 waves of

@@ -15,7 +15,7 @@ def das():
 
 @pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256), (520, 16512, 192), (257, 16384, 64), (560, 16640, 192),
                                    (40, 320, 1024), (300, 256, 3584), (530, 192, 3136), (64, 128, 16448), (513, 96, 16384),
-                                   (600, 16384, 64), (1030, 16448, 320)])
+                                   (600, 16384, 64), (1030, 16448, 320), (320, 16400, 128), (450, 16384, 192)])
 def test_mfma_gemm_against_fp64(das, M, N, K):
     rng = np.random.default_rng(M * 7 + N)
     a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
@@ -46,7 +46,7 @@ def test_gate_up_silu_epilogue_against_fp64(das, M, F, K):
     np.testing.assert_allclose(got, ref, rtol=2.0 ** -8, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
 
 
-@pytest.mark.parametrize("M,N,K", [(5, 16384, 128), (300, 16640, 192), (530, 16400, 128), (1088, 16384, 256)])
+@pytest.mark.parametrize("M,N,K", [(5, 16384, 128), (272, 16512, 128), (470, 16512, 128), (300, 16640, 192), (530, 16400, 128), (1088, 16384, 256)])
 def test_row_maximum_epilogue_against_fp64(das, M, N, K):
     """The LM-head GEMM of a greedy pass keeps only the lowest column of each row's maximum: equal to the argmax of
     the fp64 product wherever its top two values are further apart than the fp32 accumulation error; planted ties
