@@ -200,7 +200,8 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         const int nchunk = (pb.start + pb.n + chunk_tokens - 1) / chunk_tokens;
         b_prow[b] = (int)prow; b_nchunk[b] = nchunk;
         prow += (size_t)nchunk * nrb;
-        for (int rb = 0; rb < nrb; ++rb) { mblk.push_back(b); mblk.push_back(rb); }
+        if (nchunk > 1)      // (one chunk: the attention kernel writes the finished rows itself)
+            for (int rb = 0; rb < nrb; ++rb) { mblk.push_back(b); mblk.push_back(rb); }
         // two kernel shapes: up to 8 row blocks of 16 query rows per KV head (2 per wave), or up to 16 (4 per wave).
         // One launch for everything up to 8 blocks lets short sequences fill the tail of the long ones.
         const int cls = nrb <= 8 ? 1 : 2;
@@ -271,7 +272,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)
-                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_h, kl, vl, m->part_o, m->part_ml, dm, st);
+                launch_attn(pm, dptr(item_ptr[c]), (int)items[c].size() / 2, 1 << c, m->q_h, kl, vl, m->part_o, m->part_ml, m->attn, dm, st);
         }
         { ProfScope ps(m, KC_ATTN_MERGE); launch_attn_merge(pm, m->part_o, m->part_ml, m->attn, dm, st); }
         {

@@ -112,9 +112,11 @@ void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
                  float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr);
 int gemm_slices(int K, int *slice_tiles);
-// split-KV partial attention for the items of one row-block class, then the merge
+// split-KV partial attention for the items of one row-block class, then the merge.  Sequences of one chunk are finished
+// by launch_attn itself (their rows go straight to out_frag, bit-equal to what the merge would write), so pm.mblk lists
+// only the row blocks of sequences with two or more chunks.
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,
-                 const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml,
+                 const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml, bf16_t *out_frag,
                  const DasDims &dm, hipStream_t st);
 void launch_attn_merge(const PassMeta &pm, const uint16_t *part_o, const float *part_ml, bf16_t *out_frag,
                        const DasDims &dm, hipStream_t st);

@@ -53,6 +53,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
                                                            const f16_t *__restrict__ kpool,
                                                            const f16_t *__restrict__ vpool,
                                                            uint16_t *__restrict__ part_o, float *__restrict__ part_ml,
+                                                           bf16_t *__restrict__ out,
                                                            int Hkv, int G, int qstride, float scale_log2e) {
     constexpr int KFR = D / 32;            // K fragments (1 KiB) per page
     constexpr int VDB = D / 16;            // V dim blocks (512 B) per page
@@ -277,7 +278,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
     // Partials of a long sequence (many chunks) leave with non-temporal stores: they are many, the merge reads each once,
     // and kept in the caches they cost the KV stream more than the merge gains (contexts of 32k-64k: attention -20 us,
     // merge +7 us per layer); the few partials of short sequences stay cached for the merge.
-    const bool stream_out = pm.b_nchunk[b] >= 8;
+    const int nchunk_b = pm.b_nchunk[b];
+    const bool stream_out = nchunk_b >= 8;
+    // A sequence of one chunk needs no merge: its rows are finished here with the arithmetic attn_merge_kernel would
+    // apply to that one chunk ((o * l) * (1 / l) on the binary16-rounded o, then bf16), so a row comes out the same
+    // whether its sequence had one chunk or more (later chunks that the row cannot see are skipped by the merge).
+    const bool single = nchunk_b == 1;
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
         float l = l_run[i];
@@ -286,8 +292,29 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         const int rb = wave * RBW + i;
         if (rb < nrb && DBG != 7) {
             const size_t id = ((size_t)pm.b_prow[b] + (size_t)chunk * nrb + rb) * Hkv + kvh;
-            if ((lane >> 4) == 0) *reinterpret_cast<float2 *>(part_ml + id * 32 + 2 * lane) = make_float2(m_run[i], l);
             const float inv = l > 0.f ? 1.f / l : 0.f;
+            if (single) {
+                const int rr = rb * 16 + (lane & 15);
+                if (rr < R) {
+                    const int t = pm.b_row0[b] + rr / G, a = kvh * G + rr % G;
+                    const float invden = 1.f / l;
+                    auto fin = [&](float x, float y) -> uint32_t {      // two neighbouring dims -> two bf16
+                        const float2 o = unpack_h2(pack_h2(x, y));
+                        uint32_t u0 = __float_as_uint((o.x * l) * invden), u1 = __float_as_uint((o.y * l) * invden);
+                        u0 += 0x7FFFu + ((u0 >> 16) & 1u);
+                        u1 += 0x7FFFu + ((u1 >> 16) & 1u);
+                        return (u0 >> 16) | (u1 & 0xFFFF0000u);
+                    };
+#pragma unroll
+                    for (int db = 0; db < VDB; ++db) {
+                        const f32x4 o = acc[i][db] * inv;
+                        *reinterpret_cast<uint2 *>(out + frag_off(t, a * D + 16 * db + 4 * (lane >> 4), qstride)) =
+                            make_uint2(fin(o[0], o[1]), fin(o[2], o[3]));
+                    }
+                }
+                continue;
+            }
+            if ((lane >> 4) == 0) *reinterpret_cast<float2 *>(part_ml + id * 32 + 2 * lane) = make_float2(m_run[i], l);
             uint4 *dst = reinterpret_cast<uint4 *>(part_o + id * (16 * D)) + lane;
 #pragma unroll
             for (int q = 0; q < VDB / 2; ++q) {
@@ -311,7 +338,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
 #define DAS_ATTN_STAGES 4
 template <int D, int RBW, int DBG, int NW = 8>
 static void launch_attn_cfg(const PassMeta &pm, const int *items, int n_items, const f16_t *q_h, const f16_t *kpool_layer,
-                            const f16_t *vpool_layer, uint16_t *part_o, float *part_ml, const DasDims &dm, float sc, hipStream_t st) {
+                            const f16_t *vpool_layer, uint16_t *part_o, float *part_ml, bf16_t *out_frag, const DasDims &dm, float sc, hipStream_t st) {
     // 8 waves per workgroup: the 8 (or 16) query-row blocks of a KV head are spread one (two) per wave, two
     // workgroups per CU, so that MFMA, exp and LDS work of different waves overlap
     auto kern = attn_partial_kernel<D, RBW, DAS_ATTN_STAGES, (RBW == 1 ? 4 : 2), NW, DBG>;
@@ -321,15 +348,15 @@ static void launch_attn_cfg(const PassMeta &pm, const int *items, int n_items, c
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
     }
-    kern<<<dim3(n_items), dim3(NW * 64), LDS, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm.Hkv, dm.G, dm.Hq * dm.D, sc);
+    kern<<<dim3(n_items), dim3(NW * 64), LDS, st>>>(pm, items, q_h, kpool_layer, vpool_layer, part_o, part_ml, out_frag, dm.Hkv, dm.G, dm.Hq * dm.D, sc);
 }
 
 void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, const f16_t *q_h,
-                 const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml,
+                 const f16_t *kpool_layer, const f16_t *vpool_layer, uint16_t *part_o, float *part_ml, bf16_t *out_frag,
                  const DasDims &dm, hipStream_t st) {
     if (n_items <= 0) return;
     const float sc = 1.4426950408889634f / sqrtf((float)dm.D);
-#define ATTN_ARGS pm, items, n_items, q_h, kpool_layer, vpool_layer, part_o, part_ml, dm, sc, st
+#define ATTN_ARGS pm, items, n_items, q_h, kpool_layer, vpool_layer, part_o, part_ml, out_frag, dm, sc, st
 #ifdef DAS_ATTN_DEV
     // Development build only (-DDAS_ATTN_DEV): variants that leave parts of the kernel out, to time copies and
     // arithmetic separately.  Their results are wrong by design.  Selected by the DAS_ATTN_DBG environment variable.
