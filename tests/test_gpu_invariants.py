@@ -112,6 +112,26 @@ def test_logit_rows_do_not_depend_on_the_size_of_the_pass(shape):
     dm.free()
 
 
+@pytest.mark.parametrize("shape,ctx", [(di.MODELS["tiny"], 1000), (NARROW_7B, 2030)], ids=["tiny", "7b-heads"])
+def test_rows_of_a_one_chunk_sequence_equal_the_same_rows_merged(shape, ctx):
+    """A sequence whose keys fit one attention chunk is finished by the attention kernel; with more draft rows it spills
+    into a second chunk and goes through the merge.  The rows both passes share must carry the same logit bits."""
+    k_short, k_long = 8, 30
+    das, dm = _model(shape, 1, ctx + 64, (ctx + 64) // 16 + 4, max_rows=k_long + 1, max_draft=k_long)
+    rng = np.random.default_rng(5)
+    dm.seq_create(0, ctx, 7)
+    dm.kv_synth(0, 3, 0)
+    drafts = rng.integers(0, shape.vocab, size=k_long, dtype=np.int32)
+    dm.verify_step([0], [ctx], [drafts[:k_short]])                 # ctx + 9 keys: one chunk
+    short = dm.debug_logits(0, k_short + 1)
+    dm.kv_rollback([0])
+    dm.verify_step([0], [ctx], [drafts])                           # ctx + 31 keys: past the chunk boundary
+    long = dm.debug_logits(0, k_short + 1)
+    dm.kv_rollback([0])
+    assert np.array_equal(short, long), float(np.abs(short - long).max())
+    dm.free()
+
+
 def test_rollback_reverify_and_fresh_prefill_equivalence():
     shape = di.MODELS["tiny"]
     das, dm = _model(shape, 4, 512, 64)
