@@ -27,6 +27,11 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
 
+// The same copy with the non-temporal hint, for weight tiles that only this workgroup reads (see W_ONCE in gemm_kernel).
+__device__ __forceinline__ void dma16_nt(const void *g, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(g), "s"(lds_wave_base) : "memory", "m0");
+}
+
 // WGM x WGN waves, each owning TM x TN blocks of 32x32.  A k-tile is KS MFMA k-steps (BK = 16*KS: 64 or 32).  NS LDS stages form a
 // ring: while k-tile kt is multiplied, k-tiles kt+1 .. kt+NS-2 are already in flight and the stage of
 // kt-1 is being refilled with kt+NS-1.
@@ -91,20 +96,26 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // With a single M tile (a pass of few rows) every weight byte is read by exactly one workgroup: its copies carry the
+    // non-temporal hint, so that the stream does not push the activation panel, which all workgroups share, out of L2.
+    // (Only where whole copy passes are weight passes, and not in the pipelined loop, whose launches have many rows.)
+    constexpr bool W_ONCE_OK = !PIPE && (A_UNITS % NT) == 0;
+    const bool w_once = W_ONCE_OK && tiles_m == 1;
+    auto copy = [&](int j, int kt, int stage) {
+        const uint32_t dst = (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES : lds_base + stage * STAGE_BYTES + j * NT * 16;
+        if (W_ONCE_OK && j * NT >= A_UNITS && w_once) dma16_nt(src[j] + (size_t)kt * RBU, dst);
+        else dma16(src[j] + (size_t)kt * RBU, dst);
+    };
     auto issue = [&](int kt, int stage) {                  // KS fragments = RBU uint4 per k-tile and row block
 #pragma unroll
-        for (int j = 0; j < NLOAD; ++j)
-            dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
-                                                                         : lds_base + stage * STAGE_BYTES + j * NT * 16);
+        for (int j = 0; j < NLOAD; ++j) copy(j, kt, stage);
     };
     // the copies of one k-tile, cut into KS slices that are issued between the MFMA k-steps: sixteen copies
     // issued back to back would fill the vector-memory queue and stall the wave that should be multiplying
     auto issue_slice = [&](int kt, int stage, int slice) {
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j)
-            if (j % KS == slice)
-                dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
-                                                                             : lds_base + stage * STAGE_BYTES + j * NT * 16);
+            if (j % KS == slice) copy(j, kt, stage);
     };
     // Row blocks of this wave that hold rows below M.  In the last M tile a wave whose blocks are all (or, with
     // four blocks, half) past M skips their fragment reads and MFMAs: the workgroup still copies and
@@ -484,7 +495,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // k-tiles of 32 in a five-stage ring, two workgroups per CU.  The M tiles of one weight tile run side by side on
         // one XCD, so each weight byte leaves HBM once; per weight byte only 0.75 (0.5) bytes of activations come
         // through the copy path.  Measured 10% faster at T = 272 than one 320x64 tile per weight tile.
-        if (M <= 64) launch_one<2, 2, 1, 2, 6, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
+        if (M <= 64) launch_one<2, 1, 1, 2, 6, EPI_SILU_FRAG, 2, true>(A, W, C, M, N, K, ldc, st);
         // 193..320 rows: 96x256 tiles on 4 waves of 96x64 (6 MFMAs per 5 fragment reads against 2 per 3), pipelined k loop,
         // seven stages of 22 KiB (six tiles in flight per CU): 121 -> 106 us per layer at T = 272
         else if (M > 192) {
