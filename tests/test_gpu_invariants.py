@@ -77,7 +77,12 @@ def test_gpu_speculative_rounds_equal_gpu_plain_decoding(shape, ctxs):
 LONG_FFN = di.ModelShape("longffn", 2, 256, 4, 2, 64, 8448, 2048, rope_theta=1.0e4)
 
 
-@pytest.mark.parametrize("shape", [di.MODELS["tiny"], NARROW_7B, LONG_FFN], ids=["tiny", "7b-heads", "long-ffn"])
+# a model dimension of 1024: QKV, O and down all sum K in two slices -- over workgroups in passes of up to 512 rows (the QKV
+# partials are then added by the rotation kernel), folded in registers above
+WIDE_D = di.ModelShape("wided", 2, 1024, 8, 2, 128, 1024, 2048, rope_theta=1.0e4)
+
+
+@pytest.mark.parametrize("shape", [di.MODELS["tiny"], NARROW_7B, LONG_FFN, WIDE_D], ids=["tiny", "7b-heads", "long-ffn", "wide-d"])
 def test_logit_rows_do_not_depend_on_the_size_of_the_pass(shape):
     """The logits of a sequence's rows are the same bits whether it is verified alone (16 rows), in a batch of 13
     (208 rows), of 40 (640 rows) or of 70 (1120 rows): every launch-shape threshold of the row-wise kernels and of the
