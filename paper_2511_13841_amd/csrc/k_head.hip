@@ -100,9 +100,9 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(const float *__restrict
 // One workgroup (16 waves) per sequence.  Rows j = 0..k-1: accept draft j+1 iff u_accept*Z < w(draft); the rows are tested
 // side by side, one per lane, and the first rejection is taken from a ballot.  Then an inverse-CDF draw (ascending
 // vocabulary order) from the row where the walk stopped, with the rejected draft's weight removed: wave w owns the
-// contiguous segment [w*seg, (w+1)*seg) and walks it 64 consecutive columns at a time (coalesced), keeping the running
-// sum of an inclusive scan over the lanes, so that the cumulative sum runs in index order; the 16 segment totals are
-// added in order, and the wave whose segment holds the crossing walks it a second time to name the column.
+// contiguous segment [w*seg, (w+1)*seg) and walks it in blocks of 256 consecutive columns (four per lane), recording the
+// total of every block; the 16 segment totals are added in order, and the wave whose segment holds the crossing finds
+// the block from its recorded totals and reads that block a second time to name the column.
 __device__ __forceinline__ float wave_inclusive_scan(float v, int lane) {
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -111,6 +111,7 @@ __device__ __forceinline__ float wave_inclusive_scan(float v, int lane) {
     }
     return v;
 }
+#define SAMPLE_GROUPS 64
 __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__restrict__ logits, int V,
                                                              const int *__restrict__ tok, const int *__restrict__ b_row0,
                                                              const int *__restrict__ b_n, float inv_temp,
@@ -121,6 +122,7 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__rest
     __shared__ float seg_total[16];
     __shared__ int seg_lastnz[16];
     __shared__ int walk[2];          // accepted drafts, rejected token
+    __shared__ float grp_total[16][SAMPLE_GROUPS];
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = prefill_mode ? b : b_row0[b];
     const int k = prefill_mode ? 0 : b_n[b] - 1;
@@ -152,19 +154,49 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__rest
     const float *x = logits + (size_t)r * V;
     const float mx = stats[2 * r];
     const float u = prefill_mode ? u_sample[b] : u_sample[r];
-    const int seg = (((V + 15) / 16) + 63) & ~63;          // columns per wave, a multiple of 64
+    // Columns per wave: a multiple of 256.  A wave walks its segment in blocks of 256 columns, four columns per lane (one
+    // 16-byte load when V is a multiple of 4), four blocks in flight.  The weights of a block are added as: each lane its four
+    // columns in order, then an inclusive scan over the lanes, so a running sum in index order exists at every column.
+    const int seg = (((V + 15) / 16) + 255) & ~255;
     const int lo = wave * seg, hi = min(lo + seg, V);
-    auto weight = [&](int i) { return (i < hi && i != rejected) ? __expf((x[i] - mx) * inv_temp) : 0.f; };
-    float run = 0.f;
-    int nz = -1;
-    for (int base = lo; base < hi; base += 256) {          // four loads in flight per lane; the sums stay in index order
-        float w[4];
+    const int nblk = hi > lo ? (hi - lo + 255) >> 8 : 0;          // blocks of this wave that hold columns
+    const int grp = ((seg >> 8) + SAMPLE_GROUPS - 1) / SAMPLE_GROUPS;      // blocks per recorded total (1 up to V = 262144)
+    const bool vec = (V & 3) == 0;
+    auto weights4 = [&](int i, float w[4]) {
+        float l[4];
+        if (vec && i + 3 < hi) {
+            const float4 v = *reinterpret_cast<const float4 *>(x + i);
+            l[0] = v.x; l[1] = v.y; l[2] = v.z; l[3] = v.w;
+        } else {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) w[q] = weight(base + 64 * q + lane);
+            for (int e = 0; e < 4; ++e) l[e] = i + e < hi ? x[i + e] : -INFINITY;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (i + e < hi && i + e != rejected) ? __expf((l[e] - mx) * inv_temp) : 0.f;
+    };
+    float run = 0.f, gsum = 0.f;
+    int nz = -1;
+    for (int b0 = 0; b0 < nblk; b0 += 4) {
+        float w[4][4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (w[q] > 0.f) nz = base + 64 * q + lane;
-            run += __shfl(wave_inclusive_scan(w[q], lane), 63);
+            if (b0 + q < nblk) weights4(lo + ((b0 + q) << 8) + 4 * lane, w[q]);
+            else w[q][0] = w[q][1] = w[q][2] = w[q][3] = 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int blk = b0 + q;
+            if (blk >= nblk) break;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (w[q][e] > 0.f) nz = lo + (blk << 8) + 4 * lane + e;
+            const float ls = ((w[q][0] + w[q][1]) + w[q][2]) + w[q][3];
+            gsum += __shfl(wave_inclusive_scan(ls, lane), 63);
+            if (blk % grp == grp - 1 || blk == nblk - 1) {
+                if (lane == 0) grp_total[wave][blk / grp] = gsum;
+                run += gsum;
+                gsum = 0.f;
+            }
         }
     }
     for (int o = 32; o > 0; o >>= 1) nz = max(nz, __shfl_xor(nz, o));
@@ -190,11 +222,37 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__rest
     if (wave == (owner < 0 ? 0 : owner)) {
         int pick = -1;
         if (owner >= 0) {
+            // the recorded totals name the group of blocks that holds the crossing; only that group is read again
             float c = before;
-            for (int base = lo; base < hi && pick < 0; base += 64) {
-                const float sc = wave_inclusive_scan(weight(base + lane), lane);
+            const int ngrp = (nblk + grp - 1) / grp;
+            int g = 0;
+            for (; g < ngrp; ++g) {
+                const float t = grp_total[wave][g];
+                if (c + t > target) break;
+                c += t;
+            }
+            for (int blk = g * grp; g < ngrp && blk < min((g + 1) * grp, nblk) && pick < 0; ++blk) {
+                float w[4];
+                const int i = lo + (blk << 8) + 4 * lane;
+                weights4(i, w);
+                const float p0 = w[0], p1 = p0 + w[1], p2 = p1 + w[2], ls = p2 + w[3];
+                const float sc = wave_inclusive_scan(ls, lane);
+                float ex = __shfl_up(sc, 1);
+                if (lane == 0) ex = 0.f;
+                // this lane's candidate: its first column whose running sum passes the target, else its last non-zero one
+                const float pre[4] = {p0, p1, p2, ls};
+                int cand = -1;
+#pragma unroll
+                for (int e = 3; e >= 0; --e)
+                    if (w[e] > 0.f && (cand < 0 || c + (ex + pre[e]) > target)) cand = e;
                 const unsigned long long m = __ballot(c + sc > target);
-                if (m) pick = base + __ffsll((long long)m) - 1;
+                if (m) {
+                    const int L = __ffsll((long long)m) - 1;
+                    // (a lane of zero weights cannot be the first to pass, except by rounding in the scan: then the
+                    // nearest lane below it that holds a weight)
+                    const unsigned long long have = __ballot(cand >= 0) & ((2ull << L) - 1ull);
+                    if (have) pick = __shfl(i + cand, 63 - __clzll((long long)have));
+                }
                 c += __shfl(sc, 63);
             }
             // the running sum starts at the segments before this one here and at zero in the first walk: if that rounds

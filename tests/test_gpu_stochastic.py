@@ -132,3 +132,44 @@ def test_first_emitted_token_distribution_chi_square_on_gpu():
     assert chi2.sf(stat, shape.vocab - 1) > 1e-3, stat
     assert abs(n_acc / n - p[d1]) < 4 * np.sqrt(p[d1] * (1 - p[d1]) / n) + 0.01
     dm.free()
+
+
+@pytest.mark.parametrize("V", [30, 1000, 270001, 300004])
+def test_inverse_cdf_walk_against_fp64_prefix_sums_of_the_gpu_logits(V):
+    """The sampler alone: its token against fp64 prefix sums over the weights of the logits the GPU itself wrote, so the
+    window is the fp32 summation error and not the GEMM's.  Vocabularies off the 16-byte load path (not a multiple of 4),
+    below one block of 256 columns, and above 262144 (several blocks per recorded total); uniforms from 0 to just
+    below 1; both the residual draw after a rejection (the rejected token must never come back) and the draw after
+    the last accepted draft."""
+    import paper_2511_13841_amd as das
+    shape = di.ModelShape(f"v{V}", 1, 64, 2, 1, 64, 64, V, rope_theta=1.0e4)
+    blob = di.weights_bf16(shape, seed=3, sigma=0.3)
+    B, tau = 48, 0.8
+    dm = das.DasModel(das.config_for(shape, max_seqs=B, max_ctx=64, max_rows=B * 2, max_draft=1, num_pages=B * 2), blob,
+                      keep_logits=True)
+    prompt = di.prompts([9], shape.vocab, 2)[0]
+    ids = list(range(B))
+    dm.prefill(ids, [prompt] * B)
+    dm.seq_rewind(ids, [9] * B, [5] * B)
+    dm.verify_step(ids, [9] * B, [[] for _ in ids])
+    d1 = int(np.argmax(dm.debug_logits()[0]))                      # a draft with visible weight
+    dm.kv_rollback(ids)
+    u_spread = np.linspace(0.0, 1.0, B, endpoint=False, dtype=np.float64)
+    u_spread[-1] = 1.0 - 2.0 ** -24
+    for accept in (False, True):
+        ua = np.full(2 * B, 0.0 if accept else 1.0 - 2.0 ** -24, np.float32)
+        us = np.repeat(u_spread, 2).astype(np.float32)
+        print("V", V, "accept", accept, flush=True)
+        acc, nx = dm.verify_step(ids, [9] * B, [[d1]] * B, sampling=(tau, ua, us))
+        glog = dm.debug_logits()
+        dm.kv_rollback(ids)
+        for i in range(B):
+            assert int(acc[i]) == int(accept)
+            row = 2 * i + int(acc[i])
+            l = glog[row].astype(np.float64)
+            w = np.exp((l - l.max()) / tau)
+            if not accept:
+                w[d1] = 0.0
+                assert int(nx[i]) != d1
+            _check_sampled_token(w, float(us[row]), int(nx[i]), 1e-4)
+    dm.free()
