@@ -130,33 +130,11 @@ def cpu_baseline(ro, budget_s=20.0):
                       f"{secs:.1f}s of CPU time"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--context", default="synth", choices=["synth", "prefill"])
-    ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--layers", type=int, default=None)
-    ap.add_argument("--drafts", default="trajectory", choices=["trajectory", "random"],
-                    help="random: uniform random drafts, no plain-decoding pass (same kernel shapes; for profiler runs)")
-    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
-                    help="also launch a plain copy kernel of this size 3 times (profiler byte-counter reference)")
-    ap.add_argument("--faithful", action="store_true",
-                    help="stochastic workload: honest accept uniforms everywhere (acceptance ~0 on random-init weights)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--rollback", action="store_true", help="roll every step back instead of committing it (contexts stay fixed; also for development kernels whose outputs are not valid)")
-    ap.add_argument("--no-profile", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (sequences shard by data parallelism without any "
-                 "exchange; there is no multi-GPU path to time).  Use --gpus 1.")
+def measure(args, name, K, W, with_cpu_baseline):
+    """K timed rounds of one workload (after W warm-up rounds) and the same K rounds again with per-launch events.
+    Returns the fields of the bench line that belong to this workload."""
     import torch
-    if not torch.cuda.is_available():
-        sys.exit("bench.py needs an MI355X; no HIP device is visible")
-    wl = di.WORKLOADS[args.workload]
-    K, W = args.steps, args.warmup
+    wl = di.WORKLOADS[name]
     ro = Rollout(wl, batch=args.batch, n_layers=args.layers, context=args.context, max_steps=W + 2 * K + 1)
     ro.faithful = args.faithful
     ro.rollback = args.rollback
@@ -168,11 +146,12 @@ def main():
     for _ in range(W):
         ro.step()
     torch.cuda.synchronize()
-    emitted = accepted = rows = 0
+    emitted = accepted = rows = kv_read = 0
     t0 = time.perf_counter()
     for _ in range(K):
+        T, kv = ro.step_shape()
         ks, acc, _ = ro.step()
-        emitted += int((acc + 1).sum()); accepted += int(acc.sum()); rows += int((ks + 1).sum())
+        emitted += int((acc + 1).sum()); accepted += int(acc.sum()); rows += T; kv_read += kv
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -210,23 +189,93 @@ def main():
         das.debug_copy(args.calibrate_copy << 20, 3)
 
     cpu = None
-    if not args.no_cpu_baseline and args.drafts == "trajectory" and wl.mode == "greedy":
+    if with_cpu_baseline and args.drafts == "trajectory" and wl.mode == "greedy":
         cpu = cpu_baseline(ro)
 
+    # whole-step figures: algorithmic bytes of a step = every matrix once + the KV of every visible position once + the
+    # new rows' KV written; its floor = (GEMMs at the matrix peak, or at the weight stream below the ridge) + KV stream
+    shape = ro.shape
+    ms = dt / K * 1e3
+    w_bytes = 2.0 * shape.streamed_params
+    kv_bytes = (kv_read / K + rows / K) * shape.kv_bytes_per_token
+    gemm_floor = max(2.0 * (rows / K) * shape.streamed_params / (MFMA_BF16_PEAK_TFLOPS * 1e12), w_bytes / (HBM_PEAK_GBS * 1e9))
+    floor_ms = (gemm_floor + kv_bytes / (HBM_PEAK_GBS * 1e9)) * 1e3
     out = {
-        "metric": "accepted tokens/s per MI355X in batched spec-verify; % of HBM roofline",
-        "value": emitted / dt, "unit": "emitted tokens/s (accepted drafts + the target's own token per round)",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt / K * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "value": emitted / dt, "ms_per_step": ms,
         "config": {"workload": f"{wl.name}: {wl.model} decoder, batch {ro.B}, lengths {wl.lengths}, budgets {wl.budgets}, "
                                f"drafter acceptance p={wl.accept_p}, context={args.context}"
                                + (f", layers={args.layers}" if args.layers else ""),
                    "rows_per_step": rows / K, "kv_tokens": int(ro.ctx0.sum())},
         "accepted_draft_tokens_per_s": accepted / dt,
         "mean_accept_len": accepted / (K * ro.B),
+        "whole_step": {"algorithmic_bytes": w_bytes + kv_bytes, "hbm_frac": (w_bytes + kv_bytes) / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                       "floor_ms": floor_ms, "floor_over_time": floor_ms / ms},
+        "context_s": ro.context_s, "context_tokens_per_s": int(ro.ctx0.sum()) / ro.context_s if args.context == "prefill" else None,
         "roofline": roof, "roofline_attention": roof_attn, "cpu_baseline": cpu,
         "ms_per_step_with_events": ms_prof, "kernels": kernels,
     }
+    ro.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--also", default=None,
+                    help="comma-separated further workloads timed after the headline one and reported under `workloads` "
+                         "(default: c4,c2,c5 when the headline is c3 with default settings; 'none' for none)")
+    ap.add_argument("--context", default="synth", choices=["synth", "prefill"])
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--drafts", default="trajectory", choices=["trajectory", "random"],
+                    help="random: uniform random drafts, no plain-decoding pass (same kernel shapes; for profiler runs)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also launch a plain copy kernel of this size 3 times (profiler byte-counter reference)")
+    ap.add_argument("--faithful", action="store_true",
+                    help="stochastic workload: honest accept uniforms everywhere (acceptance ~0 on random-init weights)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rollback", action="store_true", help="roll every step back instead of committing it (contexts stay fixed; also for development kernels whose outputs are not valid)")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (sequences shard by data parallelism without any "
+                 "exchange; there is no multi-GPU path to time).  Use --gpus 1.")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs an MI355X; no HIP device is visible")
+    K, W = args.steps, args.warmup
+    plain = args.batch is None and args.layers is None and args.context == "synth" and not args.rollback and \
+        args.drafts == "trajectory" and not args.calibrate_copy and not args.faithful
+    also = args.also if args.also is not None else ("c4,c2,c5" if args.workload == "c3" and plain else "none")
+    also = [w for w in also.split(",") if w and w != "none" and w != args.workload]
+
+    head = measure(args, args.workload, K, W, with_cpu_baseline=not args.no_cpu_baseline)
+    out = {
+        "metric": "accepted tokens/s per MI355X in batched spec-verify; % of HBM roofline",
+        "value": head.pop("value"), "unit": "emitted tokens/s (accepted drafts + the target's own token per round)",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    }
+    out.update(head)
+    # the other configurations under the same clock: fewer fields, same definitions
+    others = {}
+    for name in also:
+        log(f"[bench] workload {name}")
+        r = measure(args, name, K, W, with_cpu_baseline=False)
+        kern = r.pop("kernels") or {}
+        gemms = {k: v for k, v in kern.items() if k.startswith("gemm_") and "frac" in v}
+        dom = max(gemms, key=lambda k: gemms[k]["ms_per_step"]) if gemms else None
+        others[name] = {
+            "ms_per_step": r["ms_per_step"], "emitted_tokens_per_s": r["value"], "accepted_draft_tokens_per_s": r["accepted_draft_tokens_per_s"],
+            "steps": K, "warmup": W, "config": r["config"], "whole_step": r["whole_step"],
+            "attention": r["roofline_attention"] and {k: r["roofline_attention"][k] for k in ("achieved", "peak", "unit", "frac", "ms_per_launch", "share_of_step")},
+            "dominant_gemm": dom and {"kernel": dom, **{k: gemms[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac", "ms_per_launch")}},
+            "kernels_ms_per_step": {k: v["ms_per_step"] for k, v in kern.items()},
+        }
+    out["workloads"] = others
     print(json.dumps(out))
 
 

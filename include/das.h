@@ -66,23 +66,30 @@ typedef struct {
     const float *u_sample;
 } das_sampling;
 
-/* Random-init (or any) weights.  `weights_bf16` is the canonical blob, every
- * matrix [out_features][in_features] row-major, bf16 bit patterns:
- *   embed[V][d]; per layer g1[d] Wq[Hq*D][d] Wk[Hkv*D][d] Wv[Hkv*D][d] Wo[d][Hq*D]
- *   g2[d] Wg[F][d] Wu[F][d] Wd[d][F]; then gf[d] Wlm[V][d].
- * The library repacks it on the device.  `hip_stream` is a hipStream_t the
- * library should run on, or NULL to create its own.  Allocates all device
- * memory (weights, KV pool of num_pages, workspaces).  Cheap to call again:
- * an RL loop reloads weights every iteration. */
-int das_model_load(const das_config *cfg, const uint16_t *weights_bf16, void *hip_stream, das_model **out);
+/* The target model whose outputs the rollout must preserve (abstract; Sec. 5.1 names the 1.5B-8B decoder families).
+ * Weights come either from the caller or from the library's own random initialisation:
+ *  - `weights_bf16` != NULL: the canonical blob, every matrix [out_features][in_features] row-major, bf16 bit
+ *    patterns:  embed[V][d]; per layer g1[d] Wq[Hq*D][d] Wk[Hkv*D][d] Wv[Hkv*D][d] Wo[d][Hq*D] g2[d] Wg[F][d]
+ *    Wu[F][d] Wd[d][F]; then gf[d] Wlm[V][d].  `seed` is ignored.
+ *  - `weights_bf16` == NULL: every matrix ~ N(0, 0.02^2), gains 1.0, generated ON THE DEVICE from `seed` by a
+ *    counter-based generator: element i of tensor t (t counts the tensors of the blob above in order) is
+ *    bf16(0.02 * sqrt(-2 ln u1) cos(2 pi u2)) with (u1, u2) the two 32-bit halves of
+ *    mix(mix(mix(seed ^ 0x5745494748545321) ^ t) ^ i), u1 = (hi + 1) / 2^32, u2 = lo / 2^32, mix = splitmix64 step,
+ *    arithmetic in fp64.  No host blob is needed (15 GB for the 7B shape).
+ * The library repacks the matrices on the device.  `hip_stream` is a hipStream_t the library should run on, or NULL
+ * to create its own.  Allocates all device memory here (weights, KV pool of num_pages, workspaces sized from
+ * max_rows / max_seqs / max_ctx): no later call on the verification path allocates.  Cheap to call again: an RL
+ * loop reloads the policy's weights every iteration (Sec. 1: the target model keeps changing during training). */
+int das_model_load(const das_config *cfg, uint64_t seed, const uint16_t *weights_bf16, void *hip_stream, das_model **out);
 int das_model_free(das_model *m);
 
-/* Prefill n NEW sequences (ids must be unused).  tokens = concatenated prompts,
- * lens[i] >= 1.  Writes KV for every prompt position and returns the first
- * pending token of each sequence (greedy argmax, lowest index on ties; or, with
- * sampling, an inverse-CDF draw from softmax(logits/T) using u_sample[i], one
- * value per SEQUENCE; u_accept unused).  Sequences end COMMITTED with
- * ctx_len = lens[i]. */
+/* Prefill: the prompt of a rollout request enters the KV cache before the first speculative round (Fig. 3: the
+ * rollout phase starts from the prompts of the batch).  n NEW sequences (ids must be unused).  tokens =
+ * concatenated prompts, lens[i] >= 1.  Writes KV for every prompt position and returns the first pending token
+ * of each sequence (greedy argmax, lowest index on ties; or, with sampling, an inverse-CDF draw from
+ * softmax(logits/T) using u_sample[i], one value per SEQUENCE; u_accept unused).  Sequences end COMMITTED with
+ * ctx_len = lens[i].  The prompt runs through the same kernels as a verification pass, in blocks of rows that
+ * attend causally to what is already written. */
 int das_prefill(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *tokens, const int32_t *lens,
                 const das_sampling *sampling, int32_t *next_token);
 
@@ -108,13 +115,15 @@ int das_verify_step(das_model *m, int32_t n, const int32_t *seq_ids, const int32
  * of the drafts depend only on the input tokens). */
 int das_kv_commit(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *accept_lens,
                   const int32_t *next_tokens);
-/* Discard every row of the pending step; ctx_len and the pending token are unchanged. */
+/* The other outcome of a round (Fig. 3 right: only accepted tokens advance generation): discard every row of the
+ * pending step; ctx_len and the pending token are unchanged, the pages taken for the step are returned. */
 int das_kv_rollback(das_model *m, int32_t n, const int32_t *seq_ids);
 /* Truncate COMMITTED sequences to an earlier committed length new_lens[i] <= ctx_len (KV beyond it is
  * discarded, pages returned) and set their pending tokens: replaying a rollout from a checkpoint. */
 int das_seq_rewind(das_model *m, int32_t n, const int32_t *seq_ids, const int32_t *new_lens,
                    const int32_t *pending_tokens);
-/* Release sequences (any state) and their pages. */
+/* A finished rollout leaves the batch (Sec. 3, Fig. 1: the effective batch shrinks as short responses end):
+ * release sequences (any state) and their pages. */
 int das_seq_free(das_model *m, int32_t n, const int32_t *seq_ids);
 
 /* ---- state injection: contexts whose KV is an input rather than a prefill ---- */
@@ -152,6 +161,11 @@ int das_debug_row_argmax(das_model *m, int32_t *out);
 int das_debug_seq(das_model *m, int32_t seq_id, int32_t *ctx_len, int32_t *pending, int32_t *state,
                   int32_t *pages, int32_t *n_pages);
 int das_debug_free_pages(das_model *m, int64_t *n_free);
+/* KV pages keep bf16-rounded values in binary16 containers (see das_kv_import): a K or V element whose bf16 value
+ * exceeds 65504 in magnitude is stored as +-65504.  Every such store (by a verification / prefill pass or by
+ * das_kv_import) is counted in a per-model counter that is never cleared; *count receives it.  Zero means that
+ * the cache holds exactly the bf16 values that were computed. */
+int das_debug_kv_saturated(das_model *m, int64_t *count);
 /* Stand-alone run of the MFMA GEMM kernel the projections use: c[M][N] (fp32) = a[M][K] * w[N][K]^T,
  * a and w row-major bf16, K a multiple of 8.  Needs no model. */
 int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c);
@@ -162,6 +176,16 @@ int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uin
  * pass, which writes no logits.  Pass F = 0 or N = 0 (and NULLs) to skip one of them.  Needs no model. */
 int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a, int32_t F, const uint16_t *wg, const uint16_t *wu,
                              float *act, int32_t N, const uint16_t *w, int32_t *col);
+
+/* Device time of the projection GEMM of one launch shape, as a verification pass launches it: epi 1 = residual add
+ * (O, down: includes the kernel that adds the K-slice partials and applies the RMSNorm that follows), 2 = gate/up
+ * with SiLU (N counts gate and up rows together), 3 = fp32 out (QKV), 4 = row maximum (LM head of a greedy pass).
+ * Operands are random bf16 (N(0,1) activations, N(0,0.02^2) weights) generated on the device; `weight_sets`
+ * distinct weight matrices are used in turn so that a launch does not find its weights in a cache left by the
+ * previous one (a decoder touches each layer's weights once per pass).  *us_per_launch = mean over `iters`
+ * launches after two warm-up launches.  Needs no model. */
+int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t iters, int32_t weight_sets,
+                        double *us_per_launch);
 
 /* Device-to-device copy of `bytes` (multiple of 16) by a trivial kernel, `repeats` times: a dispatch of
  * known HBM traffic (bytes read + bytes written) against which profiler byte counters are scaled. */

@@ -46,7 +46,7 @@ def lib():
         L = C.CDLL(_SO)
         P, I, VP = C.c_void_p, C.c_int32, C.c_void_p
         sig = {
-            "das_model_load": [C.POINTER(das_config), VP, VP, C.POINTER(P)],
+            "das_model_load": [C.POINTER(das_config), C.c_uint64, VP, VP, C.POINTER(P)],
             "das_model_free": [P],
             "das_prefill": [P, I, VP, VP, VP, C.POINTER(das_sampling), VP],
             "das_verify_step": [P, I, VP, VP, VP, VP, C.POINTER(das_sampling), VP, VP],
@@ -64,6 +64,8 @@ def lib():
             "das_debug_row_argmax": [P, VP],
             "das_debug_seq": [P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I), VP, C.POINTER(I)],
             "das_debug_free_pages": [P, C.POINTER(C.c_int64)],
+            "das_debug_kv_saturated": [P, C.POINTER(C.c_int64)],
+            "das_debug_gemm_time": [I, I, I, I, I, I, C.POINTER(C.c_double)],
             "das_debug_gemm": [I, I, I, VP, VP, VP],
             "das_debug_gemm_epilogues": [I, I, VP, I, VP, VP, VP, I, VP, VP],
             "das_debug_copy": [C.c_int64, I],
@@ -146,6 +148,13 @@ def debug_gemm_rowmax(a_bf16, w_bf16):
     return col
 
 
+def debug_gemm_time(epi, M, N, K, iters=20, weight_sets=4):
+    """Mean device time (us) of one projection GEMM launch of this shape; epi: 1 residual, 2 gate/up, 3 fp32 out, 4 row max."""
+    us = C.c_double()
+    _chk(lib().das_debug_gemm_time(int(epi), int(M), int(N), int(K), int(iters), int(weight_sets), C.byref(us)), "das_debug_gemm_time")
+    return us.value
+
+
 def debug_copy(nbytes, repeats=1):
     _chk(lib().das_debug_copy(int(nbytes), int(repeats)), "das_debug_copy")
 
@@ -153,9 +162,10 @@ def debug_copy(nbytes, repeats=1):
 class DasModel:
     """Owner of one das_model handle.  Methods carry the C names without the das_ prefix."""
 
-    def __init__(self, cfg, weights_bf16, stream=None, keep_logits=False):
+    def __init__(self, cfg, weights_bf16=None, stream=None, keep_logits=False, seed=0):
+        """weights_bf16: the canonical blob, or None to let the library draw N(0, 0.02^2) weights from `seed` on the device."""
         self.cfg = cfg
-        w = np.ascontiguousarray(weights_bf16, dtype=np.uint16)
+        w = np.ascontiguousarray(weights_bf16, dtype=np.uint16) if weights_bf16 is not None else None
         h = C.c_void_p()
         if stream is None:
             try:                                   # PyTorch only lends its current HIP stream
@@ -164,7 +174,8 @@ class DasModel:
                     stream = torch.cuda.current_stream().cuda_stream
             except Exception:
                 stream = None
-        _chk(lib().das_model_load(C.byref(cfg), w.ctypes.data, C.c_void_p(stream or 0), C.byref(h)), "das_model_load")
+        _chk(lib().das_model_load(C.byref(cfg), int(seed), w.ctypes.data if w is not None else None, C.c_void_p(stream or 0), C.byref(h)),
+             "das_model_load")
         self.h = h
         if keep_logits:
             self.keep_logits(True)
@@ -275,6 +286,11 @@ class DasModel:
         pages = np.empty(n.value, np.int32)
         _chk(lib().das_debug_seq(self.h, int(seq_id), None, None, None, pages.ctypes.data, None), "das_debug_seq")
         return dict(ctx_len=c.value, pending=p.value, state=s.value, pages=pages.tolist())
+
+    def debug_kv_saturated(self):
+        n = C.c_int64()
+        _chk(lib().das_debug_kv_saturated(self.h, C.byref(n)), "das_debug_kv_saturated")
+        return n.value
 
     def debug_free_pages(self):
         n = C.c_int64()

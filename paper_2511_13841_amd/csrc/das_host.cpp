@@ -62,7 +62,9 @@ struct das_model {
     size_t gemm_ws_floats = 0;
     uint16_t *part_o = nullptr;      // split-KV partial outputs (fp16, normalised per chunk)
     float *part_ml = nullptr;        // their (m, l) per row
-    size_t part_rows_cap = 0;
+    size_t part_rows_cap = 0;        // 16-row blocks the partial buffers hold (fixed at load)
+    int max_blocks = 0;              // most blocks one pass may have (sequences + extra prompt blocks of a prefill pass)
+    unsigned long long *d_kv_sat = nullptr;      // K/V elements that did not fit their container, ever
     int *d_g = nullptr, *d_accept = nullptr, *d_next = nullptr;
     // staging
     int *h_stage = nullptr, *d_stage = nullptr;
@@ -149,28 +151,30 @@ static void shrink_pages(das_model *m, int slot, int tokens) {
     while ((int)s.pages.size() > pages_for(tokens)) { m->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
 }
 
-// Partials are kept per 16-row block: 16 x D accumulators in the lane order the MFMA leaves them in, and (m, l) per row.
-static int ensure_partials(das_model *m, size_t rows) {
-    if (rows <= m->part_rows_cap) return DAS_OK;
-    HIPCHK(hipStreamSynchronize(m->st));
-    size_t cap = std::max(rows, m->part_rows_cap * 2);
-    if (m->part_o) { (void)hipFree(m->part_o); (void)hipFree(m->part_ml); m->part_o = nullptr; m->part_ml = nullptr; m->part_rows_cap = 0; }
-    hipError_t e1 = hipMalloc((void **)&m->part_o, cap * m->dm.Hkv * 16 * m->dm.D * sizeof(uint16_t));
-    hipError_t e2 = hipMalloc((void **)&m->part_ml, cap * m->dm.Hkv * 32 * sizeof(float));
-    if (e1 != hipSuccess || e2 != hipSuccess) {
-        g_dev_err = "hipMalloc(attention partials) failed"; (void)hipGetLastError();
-        if (e1 == hipSuccess) (void)hipFree(m->part_o);
-        if (e2 == hipSuccess) (void)hipFree(m->part_ml);
-        m->part_o = nullptr; m->part_ml = nullptr;
-        return DAS_ERR_NOMEM;
+// Size of a pass before anything is written or changed: ints of the staging block it needs (n_upd page-table
+// updates, n_u uniforms per stream) and 16-row blocks of split-KV partials.  Partials are kept per 16-row block: 16 x D
+// accumulators in the lane order the MFMA leaves them in, and (m, l) per row.
+struct PassSize { size_t stage_ints, part_rows; };
+static PassSize pass_size(const das_model *m, const std::vector<PassBlock> &blocks, size_t n_upd, size_t n_u) {
+    const int chunk_tokens = das_attn_chunk(m->dm.Hkv);
+    size_t T = 0, items = 0, mblk = 0, prow = 0;
+    for (auto &b : blocks) {
+        const size_t nrb = ((size_t)m->dm.G * b.n + 15) / 16, nchunk = ((size_t)b.start + b.n + chunk_tokens - 1) / chunk_tokens;
+        T += b.n; items += nchunk; prow += nchunk * nrb;
+        if (nchunk > 1) mblk += nrb;
     }
-    m->part_rows_cap = cap;
+    return {4 * T + 6 * blocks.size() + 2 * items * m->dm.Hkv + 2 * mblk + 2 * n_upd + 2 * n_u, prow};
+}
+static int check_pass_size(const das_model *m, const PassSize &ps) {
+    if (ps.stage_ints > m->stage_ints) return DAS_ERR_INVALID;        // over a configured maximum
+    if (ps.part_rows > m->part_rows_cap) return DAS_ERR_NOMEM;
     return DAS_OK;
 }
 
 // ------------------------------------------------------------------------------------------------ one forward pass
 // Rows of all blocks go through the layer stack; logits (+ argmax) are produced for the
-// selected rows.  On return kernels are enqueued, nothing is synchronised.
+// selected rows.  On return kernels are enqueued, nothing is synchronised.  The caller has checked pass_size() against
+// the staging block and the partial buffers: nothing here allocates.
 static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const float *u_accept, const float *u_sample,
                     int n_u, PassMeta *pm_out, const float **d_ua, const float **d_us) {
     const DasDims &dm = m->dm;
@@ -211,7 +215,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
             if (pb.want == 2 || (pb.want == 1 && j == pb.n - 1)) sel[n_sel++] = r;
         }
     }
-    if (prow > 0x7FFFFFFFull) return DAS_ERR_NOMEM;
+    if (prow > m->part_rows_cap) return DAS_ERR_NOMEM;
     // One work item per (sequence, chunk, KV head), longest first over the whole launch so that the short last
     // chunks fill its tail; among equal lengths one KV head's items run side by side (measured faster than the
     // heads of one chunk side by side).  Entry: sequence, chunk | head << 20.
@@ -237,9 +241,6 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     float *us = reinterpret_cast<float *>(p);
     if (u_sample) { std::memcpy(p, u_sample, sizeof(float) * n_u); p += n_u; }
     const size_t used = (size_t)(p - m->h_stage);
-    if (used > m->stage_ints) return DAS_ERR_INVALID;
-    int rc = ensure_partials(m, prow);
-    if (rc != DAS_OK) return rc;
 
     hipStream_t st = m->st;
     auto dptr = [&](const void *hp) { return m->d_stage + (reinterpret_cast<const int *>(hp) - m->h_stage); };
@@ -268,7 +269,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         // (few rows: the K-slice partials of QKV stay in the workspace and the rotation kernel adds them)
         int qkv_slices = 1;
         { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats, nullptr, &qkv_slices); }
-        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, qkv_slices > 1 ? m->gemm_ws : m->qkv, qkv_slices, m->q_h, m->cs, kl, vl, dm, st); }
+        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, qkv_slices > 1 ? m->gemm_ws : m->qkv, qkv_slices, m->q_h, m->cs, kl, vl, dm, m->d_kv_sat, st); }
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)
@@ -339,8 +340,6 @@ extern "C" int das_model_free(das_model *m) {
     if (!m) return DAS_ERR_INVALID;
     (void)hipStreamSynchronize(m->st);
     for (void *p : m->allocs) (void)hipFree(p);
-    if (m->part_o) (void)hipFree(m->part_o);
-    if (m->part_ml) (void)hipFree(m->part_ml);
     if (m->h_stage) (void)hipHostFree(m->h_stage);
     if (m->h_out) (void)hipHostFree(m->h_out);
     for (auto &e : m->ev_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
@@ -350,7 +349,23 @@ extern "C" int das_model_free(das_model *m) {
     return DAS_OK;
 }
 
-static int load_impl(das_model *m, const uint16_t *wb) {
+// One tensor of the canonical blob into `dst` on the device: copied from the caller's blob, or generated there
+// (matrices N(0, 0.02^2) from the counter-based generator keyed by (seed, tensor index); gains 1.0).
+struct WeightSource {
+    const uint16_t *src; uint64_t seed, tensor = 0; hipStream_t st;
+    int next(bf16_t *dst, size_t count, bool gain) {
+        if (src) {
+            HIPCHK(hipMemcpyAsync(dst, src, count * 2, hipMemcpyHostToDevice, st));
+            HIPCHK(hipStreamSynchronize(st));
+            src += count;
+        } else if (gain) launch_fill_const(dst, count, (bf16_t)0x3F80, st);
+        else launch_fill_normal(dst, count, seed, tensor, 0.02, st);
+        ++tensor;
+        return DAS_OK;
+    }
+};
+
+static int load_impl(das_model *m, const uint16_t *wb, uint64_t seed) {
     const das_config &c = m->cfg;
     DasDims &dm = m->dm;
     dm.L = c.n_layers; dm.d = c.d_model; dm.Hq = c.n_q_heads; dm.Hkv = c.n_kv_heads; dm.D = c.head_dim;
@@ -372,33 +387,31 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     const int Vp = round_up(V, 256), qkvNp = round_up(dm.qkvN, 256), dp = round_up(d, 256), gup = round_up(2 * Fp, 256);
     A(m->wlm, (size_t)Vp * d);
     m->layers.resize(dm.L);
-    const uint16_t *src = wb;
-    HIPCHK(hipMemcpy(m->embed, src, (size_t)V * d * 2, hipMemcpyHostToDevice)); src += (size_t)V * d;
+    WeightSource ws{wb, seed, 0, m->st};
+#define W(dst, count, gain) if ((rc = ws.next((dst), (count), (gain))) != DAS_OK) return rc
+    W(m->embed, (size_t)V * d, false);
     for (int l = 0; l < dm.L; ++l) {
         LayerW &w = m->layers[l];
         A(w.g1, (size_t)d); A(w.g2, (size_t)d);
         A(w.wqkv, (size_t)qkvNp * d); A(w.wo, (size_t)dp * qd); A(w.wgu, (size_t)gup * d); A(w.wd, (size_t)dp * Fp);
-        HIPCHK(hipMemcpy(w.g1, src, (size_t)d * 2, hipMemcpyHostToDevice)); src += d;
-        // Wq, Wk, Wv are adjacent in the blob: one [qkvN][d] matrix
-        HIPCHK(hipMemcpy(tmp, src, (size_t)dm.qkvN * d * 2, hipMemcpyHostToDevice)); src += (size_t)dm.qkvN * d;
+        W(w.g1, (size_t)d, true);
+        // Wq, Wk, Wv are adjacent in the blob: one [qkvN][d] matrix made of three tensors
+        W(tmp, (size_t)qd * d, false); W(tmp + (size_t)qd * d, (size_t)kd * d, false); W(tmp + (size_t)(qd + kd) * d, (size_t)kd * d, false);
         launch_pack_weight(tmp, w.wqkv, dm.qkvN, d, qkvNp, d, m->st);
-        HIPCHK(hipStreamSynchronize(m->st));
-        HIPCHK(hipMemcpy(tmp, src, (size_t)d * qd * 2, hipMemcpyHostToDevice)); src += (size_t)d * qd;
+        W(tmp, (size_t)d * qd, false);
         launch_pack_weight(tmp, w.wo, d, qd, dp, qd, m->st);
-        HIPCHK(hipStreamSynchronize(m->st));
-        HIPCHK(hipMemcpy(w.g2, src, (size_t)d * 2, hipMemcpyHostToDevice)); src += d;
-        HIPCHK(hipMemcpy(tmp, src, (size_t)2 * F * d * 2, hipMemcpyHostToDevice)); src += (size_t)2 * F * d;
+        W(w.g2, (size_t)d, true);
+        W(tmp, (size_t)F * d, false); W(tmp + (size_t)F * d, (size_t)F * d, false);
         HIPCHK(hipMemsetAsync(w.wgu, 0, (size_t)gup * d * 2, m->st));
         launch_pack_gateup(tmp, tmp + (size_t)F * d, w.wgu, F, d, Fp, m->st);
-        HIPCHK(hipStreamSynchronize(m->st));
-        HIPCHK(hipMemcpy(tmp, src, (size_t)d * F * 2, hipMemcpyHostToDevice)); src += (size_t)d * F;
+        W(tmp, (size_t)d * F, false);
         launch_pack_weight(tmp, w.wd, d, F, dp, Fp, m->st);
-        HIPCHK(hipStreamSynchronize(m->st));
     }
-    HIPCHK(hipMemcpy(m->gf, src, (size_t)d * 2, hipMemcpyHostToDevice)); src += d;
-    HIPCHK(hipMemcpy(tmp, src, (size_t)V * d * 2, hipMemcpyHostToDevice));
+    W(m->gf, (size_t)d, true);
+    W(tmp, (size_t)V * d, false);
     launch_pack_weight(tmp, m->wlm, V, d, Vp, d, m->st);
     HIPCHK(hipStreamSynchronize(m->st));
+#undef W
     // ---- RoPE inverse frequencies theta^(-2i/D), fp64
     {
         std::vector<double> f(dm.D / 2);
@@ -427,10 +440,25 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     HIPCHK(hipMemsetAsync(m->attn, 0, Mp * qd * 2, m->st));
     HIPCHK(hipMemsetAsync(m->act, 0, Mp * Fp * 2, m->st));
     HIPCHK(hipMemsetAsync(m->xsel, 0, Mp * d * 2, m->st));
-    // ---- staging
-    const size_t max_items = (size_t)c.max_seqs * (c.max_ctx / das_attn_chunk(c.n_kv_heads) + 2);
-    m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)c.max_seqs + 2 * max_items * dm.Hkv +
-                    2 * ((size_t)c.max_rows * dm.G / 16 + (size_t)c.max_seqs) +
+    A(m->d_kv_sat, 1);
+    HIPCHK(hipMemsetAsync(m->d_kv_sat, 0, sizeof(unsigned long long), m->st));
+    // ---- split-KV partials, sized here once for every pass the configuration allows.  A block (a sequence's rows in
+    // one pass) has at most 16 row blocks of 16 query rows per KV head and one partial per chunk it spans; the chunks of
+    // distinct sequences together are bounded by the KV pool (a chunk is at most half empty per sequence).  A prefill
+    // pass that takes several blocks of ONE prompt is cut to fit this capacity by its caller.
+    const int chunk_tokens = das_attn_chunk(c.n_kv_heads);
+    m->max_blocks = c.max_seqs + c.max_rows / std::max(1, std::min(256 / dm.G, c.max_rows)) + 1;
+    {
+        const size_t pool_chunks = (size_t)c.num_pages * DAS_PAGE / chunk_tokens + (size_t)c.max_seqs;
+        const size_t per_seq_chunks = (size_t)c.max_ctx / chunk_tokens + 1;
+        m->part_rows_cap = 16 * std::min(pool_chunks, per_seq_chunks * (size_t)c.max_seqs);
+        A(m->part_o, m->part_rows_cap * dm.Hkv * 16 * dm.D);
+        A(m->part_ml, m->part_rows_cap * dm.Hkv * 32);
+    }
+    // ---- staging (see pass_size)
+    const size_t max_items = (size_t)m->max_blocks * (c.max_ctx / chunk_tokens + 2);
+    m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)m->max_blocks + 2 * max_items * dm.Hkv +
+                    2 * ((size_t)c.max_rows * dm.G / 16 + (size_t)m->max_blocks) +
                     2 * ((size_t)c.max_rows / DAS_PAGE + 2 * (size_t)c.max_seqs + 2) + 64;
     HIPCHK(hipHostMalloc((void **)&m->h_stage, m->stage_ints * sizeof(int), hipHostMallocDefault));
     A(m->d_stage, m->stage_ints);
@@ -448,8 +476,8 @@ static int load_impl(das_model *m, const uint16_t *wb) {
     return DAS_OK;
 }
 
-extern "C" int das_model_load(const das_config *cfg, const uint16_t *weights_bf16, void *hip_stream, das_model **out) {
-    if (!out || !weights_bf16) return DAS_ERR_INVALID;
+extern "C" int das_model_load(const das_config *cfg, uint64_t seed, const uint16_t *weights_bf16, void *hip_stream, das_model **out) {
+    if (!out) return DAS_ERR_INVALID;
     *out = nullptr;
     int rc = check_config(cfg);
     if (rc != DAS_OK) return rc;
@@ -464,7 +492,7 @@ extern "C" int das_model_load(const das_config *cfg, const uint16_t *weights_bf1
         if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); delete m; return DAS_ERR_DEVICE; }
         m->own_stream = true;
     }
-    rc = load_impl(m, weights_bf16);
+    rc = load_impl(m, weights_bf16, seed);
     if (rc != DAS_OK) { das_model_free(m); return rc; }
     *out = m;
     return DAS_OK;
@@ -547,20 +575,32 @@ extern "C" int das_prefill(das_model *m, int32_t n, const int32_t *seq_ids, cons
     }
     int rc = DAS_OK;
     for (int i = 0; i < n && rc == DAS_OK; ++i) rc = upload_page_row(m, slot[i]);
-    const int per_seq = std::min(256 / m->dm.G, m->cfg.max_rows);
+    // A pass takes up to max_rows prompt rows.  The attention kernel serves at most 256 query rows per KV head from one
+    // sweep over the KV, so a prompt enters as blocks of floor(256 / G) rows; several blocks of the same prompt may share
+    // a pass (a block attends to the KV that earlier blocks of the pass write in the same layer, kernel after kernel),
+    // so a long prompt streams the weights once per max_rows rows, not once per block.
+    const int per_blk = std::min(256 / m->dm.G, m->cfg.max_rows);
     int first = 0;                                   // first unfinished sequence
     while (rc == DAS_OK && first < n) {
         std::vector<PassBlock> blocks;
         std::vector<int> who;
-        int T = 0;
-        for (int i = first; i < n && T < m->cfg.max_rows && (int)blocks.size() < m->cfg.max_seqs; ++i) {
-            if (done[i] >= lens[i]) continue;
-            int rows = std::min(std::min(lens[i] - done[i], per_seq), m->cfg.max_rows - T);
-            if (rows <= 0) break;
-            blocks.push_back({slot[i], done[i], rows, base[i] + done[i], (done[i] + rows == lens[i]) ? 1 : 0});
-            who.push_back(i);
-            T += rows;
+        int T = 0, n_want = 0;
+        bool full = false;
+        for (int i = first; i < n && !full; ++i) {
+            int d0 = done[i];
+            while (d0 < lens[i]) {
+                const int rows = std::min(std::min(lens[i] - d0, per_blk), m->cfg.max_rows - T);
+                if (rows <= 0 || (int)blocks.size() >= m->max_blocks) { full = true; break; }
+                blocks.push_back({slot[i], d0, rows, base[i] + d0, (d0 + rows == lens[i]) ? 1 : 0});
+                if (check_pass_size(m, pass_size(m, blocks, m->pending_upd.size() / 2, (size_t)n_want + 1)) != DAS_OK) {
+                    blocks.pop_back(); full = true; break;      // the staging block or the partial buffers are full
+                }
+                who.push_back(i);
+                n_want += blocks.back().want ? 1 : 0;
+                T += rows; d0 += rows;
+            }
         }
+        if (blocks.empty()) { rc = DAS_ERR_NOMEM; break; }      // (one block always fits a consistent configuration)
         PassMeta pm;
         const float *d_ua = nullptr, *d_us = nullptr;
         std::vector<float> us;
@@ -629,20 +669,27 @@ extern "C" int das_verify_step(das_model *m, int32_t n, const int32_t *seq_ids, 
         need_pages += pages_for(s.ctx + 1 + draft_lens[i]) - (int64_t)s.pages.size();
     }
     if (need_pages > (int64_t)m->free_pages.size()) return DAS_ERR_NOMEM;
-
-    // ---- state changes start here
     std::vector<int32_t> rows((size_t)T);
     std::vector<PassBlock> blocks(n);
     {
         int r = 0; const int32_t *dp = draft_tokens;
         for (int i = 0; i < n; ++i) {
-            Seq &s = m->slots[slot[i]];
-            grow_pages(m, slot[i], s.ctx + 1 + draft_lens[i]);
+            const Seq &s = m->slots[slot[i]];
             blocks[i] = {slot[i], s.ctx, 1 + draft_lens[i], rows.data() + r, 2};
             rows[r++] = s.pending;
             for (int j = 0; j < draft_lens[i]; ++j) rows[r++] = *dp++;
         }
     }
+    // the pass must fit the staging block and the partial buffers (both sized at load): checked like any other argument
+    {
+        const int rc0 = check_pass_size(m, pass_size(m, blocks, m->pending_upd.size() / 2 + (size_t)std::max<int64_t>(need_pages, 0),
+                                                     sampling ? (size_t)T : 0));
+        if (rc0 != DAS_OK) return rc0;
+    }
+
+    // ---- state changes start here
+    const size_t upd_at_entry = m->pending_upd.size();
+    for (int i = 0; i < n; ++i) grow_pages(m, slot[i], m->slots[slot[i]].ctx + 1 + draft_lens[i]);
     PassMeta pm;
     const float *d_ua = nullptr, *d_us = nullptr;
     int rc = run_pass(m, blocks, sampling ? sampling->u_accept : nullptr, sampling ? sampling->u_sample : nullptr, (int)T,
@@ -663,8 +710,9 @@ extern "C" int das_verify_step(das_model *m, int32_t n, const int32_t *seq_ids, 
     }
     if (hipStreamSynchronize(m->st) != hipSuccess) { g_dev_err = "stream synchronize failed in verify"; rc = DAS_ERR_DEVICE; }
     prof_collect(m);
-    if (rc != DAS_OK) {                              // give the freshly taken pages back
-        for (int i = 0; i < n; ++i) shrink_pages(m, slot[i], m->slots[slot[i]].ctx);
+    if (rc != DAS_OK) {      // give the freshly taken pages back, and forget their page-table updates if they are still queued
+        if (m->pending_upd.size() > upd_at_entry) m->pending_upd.resize(upd_at_entry);
+        for (int i = n - 1; i >= 0; --i) shrink_pages(m, slot[i], m->slots[slot[i]].ctx);
         return rc;
     }
     for (int i = 0; i < n; ++i) {
@@ -786,7 +834,7 @@ static int kv_io(das_model *m, int mode, int32_t seq_id, int32_t layer, int32_t 
             if (fail(hipMemcpy(dk, k, cnt * 2, hipMemcpyHostToDevice))) break;
             if (fail(hipMemcpy(dv, v, cnt * 2, hipMemcpyHostToDevice))) break;
         }
-        { ProfScope ps(m, KC_KVIO); launch_kv_io(mode, prow, first_pos, n_pos, kl, vl, dk, dv, m->dm.Hkv, m->dm.D, (int)m->cfg.num_pages, m->st); }
+        { ProfScope ps(m, KC_KVIO); launch_kv_io(mode, prow, first_pos, n_pos, kl, vl, dk, dv, m->dm.Hkv, m->dm.D, (int)m->cfg.num_pages, m->d_kv_sat, m->st); }
         if (fail(hipStreamSynchronize(m->st))) break;
         if (mode == 1) {
             if (fail(hipMemcpy(k, dk, cnt * 2, hipMemcpyDeviceToHost))) break;
@@ -864,6 +912,14 @@ extern "C" int das_debug_seq(das_model *m, int32_t seq_id, int32_t *ctx_len, int
     if (state) *state = s.state;
     if (n_pages) *n_pages = (int)s.pages.size();
     if (pages) std::copy(s.pages.begin(), s.pages.end(), pages);
+    return DAS_OK;
+}
+extern "C" int das_debug_kv_saturated(das_model *m, int64_t *count) {
+    if (!m || !count) return DAS_ERR_INVALID;
+    unsigned long long c = 0;
+    HIPCHK(hipStreamSynchronize(m->st));
+    HIPCHK(hipMemcpy(&c, m->d_kv_sat, sizeof(c), hipMemcpyDeviceToHost));
+    *count = (int64_t)c;
     return DAS_OK;
 }
 extern "C" int das_debug_free_pages(das_model *m, int64_t *n_free) {
@@ -948,6 +1004,59 @@ extern "C" int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a,
         }
     } while (0);
     (void)hipFree(da); (void)hipFree(pa); (void)hipFree(dw); (void)hipFree(pw); (void)hipFree(dact); (void)hipFree(keys); (void)hipFree(dcol);
+    return rc;
+}
+
+// Device time of one projection GEMM shape with the launch configuration a pass would use (see das.h).
+extern "C" int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t iters, int32_t weight_sets, double *us_per_launch) {
+    if (M < 1 || N < 32 || K < 64 || (K % 64) || iters < 1 || weight_sets < 1 || weight_sets > 64 || !us_per_launch ||
+        (epi != EPI_RESID_F32 && epi != EPI_SILU_FRAG && epi != EPI_F32_ROWMAJOR && epi != EPI_ROWMAX) ||
+        (epi == EPI_SILU_FRAG && (N % 128)) || (epi == EPI_ROWMAX && N < 16384) || (epi != EPI_SILU_FRAG && epi != EPI_ROWMAX && (N % 4)))
+        return DAS_ERR_INVALID;
+    const size_t Mp = (size_t)round_up(M, 256) + 256, Np = (size_t)round_up(N, 256);
+    const int Fp = N / 2;      // gate/up: N counts gate and up rows together (multiple of 128, so no padding of the FFN width)
+    bf16_t *a = nullptr, *w = nullptr, *g = nullptr, *y = nullptr;
+    float *c = nullptr, *ws = nullptr;
+    unsigned long long *keys = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = DAS_OK;
+    auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
+    do {
+        int slice_tiles = 0;
+        const size_t ws_floats = (size_t)gemm_slices(K, &slice_tiles) * std::min<size_t>(M, 512) * N;
+        const size_t c_elems = epi == EPI_SILU_FRAG ? Mp * Fp / 2 + 1 : epi == EPI_ROWMAX ? 1 : (size_t)M * N;
+        if (bad(hipMalloc((void **)&a, Mp * K * 2)) || bad(hipMalloc((void **)&w, Np * K * 2 * weight_sets)) ||
+            bad(hipMalloc((void **)&c, c_elems * 4)) || bad(hipMalloc((void **)&ws, ws_floats * 4)) ||
+            bad(hipMalloc((void **)&g, (size_t)N * 2)) || bad(hipMalloc((void **)&y, Mp * N * 2)) ||
+            bad(hipMalloc((void **)&keys, (size_t)M * 8)) || bad(hipEventCreate(&e0)) || bad(hipEventCreate(&e1))) break;
+        // operands are filled directly in fragment order: the values are i.i.d., so the order is immaterial
+        launch_fill_normal(a, Mp * K, 1, 0, 1.0, nullptr);
+        launch_fill_normal(w, Np * K * weight_sets, 1, 1, 0.02, nullptr);
+        launch_fill_const(g, (size_t)N, (bf16_t)0x3F80, nullptr);
+        if (bad(hipMemset(c, 0, c_elems * 4))) break;
+        const GemmNormTail tail = {g, y, 1e-6f};
+        auto once = [&](int it) {
+            const bf16_t *wi = w + (size_t)(it % weight_sets) * Np * K;
+            if (epi == EPI_ROWMAX) {
+                launch_rowmax_keys_clear(keys, M, nullptr);
+                launch_gemm(EPI_ROWMAX, a, wi, keys, M, N, K, N, nullptr, ws, ws_floats);
+            } else if (epi == EPI_SILU_FRAG) launch_gemm(EPI_SILU_FRAG, a, wi, c, M, N, K, Fp, nullptr, ws, ws_floats);
+            else if (epi == EPI_RESID_F32) launch_gemm(EPI_RESID_F32, a, wi, c, M, N, K, N, nullptr, ws, ws_floats, (N % 64) == 0 && N <= 8192 ? &tail : nullptr);
+            else { int left = 1; launch_gemm(EPI_F32_ROWMAJOR, a, wi, c, M, N, K, N, nullptr, ws, ws_floats, nullptr, &left); }
+        };
+        once(0); once(1);
+        if (bad(hipDeviceSynchronize())) break;
+        if (bad(hipEventRecord(e0, nullptr))) break;
+        for (int it = 0; it < iters; ++it) once(it + 2);
+        if (bad(hipEventRecord(e1, nullptr)) || bad(hipEventSynchronize(e1))) break;
+        float ms = 0.f;
+        if (bad(hipEventElapsedTime(&ms, e0, e1))) break;
+        if (bad(hipGetLastError())) break;
+        *us_per_launch = (double)ms * 1e3 / iters;
+    } while (0);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(a); (void)hipFree(w); (void)hipFree(c); (void)hipFree(ws); (void)hipFree(g); (void)hipFree(y); (void)hipFree(keys);
     return rc;
 }
 

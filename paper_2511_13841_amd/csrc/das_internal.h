@@ -102,8 +102,9 @@ void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, in
 // binary16 containers (exact for 2^-17 <= |x| <= 65504; larger magnitudes saturate).
 // slices > 1: qkv points at `slices` slabs of [T][qkvN] partial sums (see launch_gemm's left_slices); the kernel adds them
 // in ascending order first, which gives the bits the GEMM's own reduce kernel would have written.
+// sat: device counter of K/V elements that did not fit the container (never cleared)
 void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h, const float *cs,
-                    f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st);
+                    f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, unsigned long long *sat, hipStream_t st);
 // C[M][N] = A[M][K] * W[N][K]^T, A and W in fragment order
 // ws: fp32 workspace of ws_floats elements for the slice partials of narrow few-row GEMMs (may be null: slower, same result)
 // left_slices (EPI_F32_ROWMAJOR only): a caller whose next kernel can add the K-slice partials itself passes a pointer.
@@ -131,7 +132,10 @@ void launch_sample(const float *logits, int V, const int *tok, const int *b_row0
                    float *row_stats, int *accept_len, int *next_token, hipStream_t st);
 // k_lin / v_lin: bf16, linear [n_pos][Hkv][D]; mode 0 imports into the pages, mode 1 exports
 void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, f16_t *kpool_layer, f16_t *vpool_layer,
-                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, hipStream_t st);
+                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, unsigned long long *sat, hipStream_t st);
 void launch_kv_synth(const int *page_row, int ctx, f16_t *kpool_layer, f16_t *vpool_layer, int Hkv, int D, int num_pages,
                      uint64_t seed, uint64_t seq_key, int layer, hipStream_t st);
 void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+// dst[i] = bf16(sigma * z_i), z_i standard normal from the counter-based generator keyed by (seed, tensor_id, i); dst[i] = v
+void launch_fill_normal(bf16_t *dst, size_t n, uint64_t seed, uint64_t tensor_id, double sigma, hipStream_t st);
+void launch_fill_const(bf16_t *dst, size_t n, bf16_t v, hipStream_t st);

@@ -218,13 +218,20 @@ __device__ __forceinline__ float h2f(f16_t u) { return (float)__builtin_bit_cast
 // The attention kernel's matrix instructions are the f16 ones: next to these values the rotated query and the
 // probabilities then carry 11 significant bits in one term.
 __device__ __forceinline__ f16_t kv_elem(float x) { return f2h(bf2f(f2bf(x))); }
+// the same store, counted in *sat when the bf16 value does not fit the container (NaN counts too): the cache then no
+// longer holds what was computed, and the caller can see it (das_debug_kv_saturated)
+__device__ __forceinline__ f16_t kv_elem_counted(float x, unsigned long long *sat) {
+    const float b = bf2f(f2bf(x));
+    if (!(fabsf(b) <= 65504.f)) atomicAdd(sat, 1ull);
+    return f2h(b);
+}
 
 // grid (T, heads / heads per workgroup), block 256 = 256 / (D/2) heads: thread i of a head owns the rotate-half pair
 // (i, i + D/2).  The projections arrive in fp32 and are rounded exactly once, after the rotation: q to binary16, k and
 // v to bf16.
 __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, int slices, size_t slab, f16_t *__restrict__ q_h,
                                const float2 *__restrict__ cs, f16_t *__restrict__ kpool, f16_t *__restrict__ vpool,
-                               int Hq, int Hkv, int D, int qkvN) {
+                               int Hq, int Hkv, int D, int qkvN, unsigned long long *__restrict__ sat) {
     const int half = D >> 1, r = blockIdx.x, hh = blockIdx.y * (256 / half) + threadIdx.x / half, i = threadIdx.x % half;
     if (hh >= Hq + 2 * Hkv) return;
     const float *row = qkv + (size_t)r * qkvN + (size_t)hh * D;
@@ -245,42 +252,42 @@ __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, int s
     int t = pos & 15;
     if (hh < Hq + Hkv) {
         f16_t *blk = kpool + ((size_t)page * Hkv + (hh - Hq)) * (size_t)(DAS_PAGE * D);
-        blk[kpage_off(t, i)] = kv_elem(x1);
-        blk[kpage_off(t, i + half)] = kv_elem(x2);
+        blk[kpage_off(t, i)] = kv_elem_counted(x1, sat);
+        blk[kpage_off(t, i + half)] = kv_elem_counted(x2, sat);
     } else {
         f16_t *blk = vpool + ((size_t)page * Hkv + (hh - Hq - Hkv)) * (size_t)(DAS_PAGE * D);
-        blk[vpage_off(t, i)] = kv_elem(x1);
-        blk[vpage_off(t, i + half)] = kv_elem(x2);
+        blk[vpage_off(t, i)] = kv_elem_counted(x1, sat);
+        blk[vpage_off(t, i + half)] = kv_elem_counted(x2, sat);
     }
 }
 void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h, const float *cs,
-                    f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, hipStream_t st) {
+                    f16_t *kpool_layer, f16_t *vpool_layer, const DasDims &dm, unsigned long long *sat, hipStream_t st) {
     const int heads_per_wg = 256 / (dm.D / 2);
     rope_kv_kernel<<<dim3(pm.T, (dm.Hq + 2 * dm.Hkv + heads_per_wg - 1) / heads_per_wg), dim3(256), 0, st>>>(
-        pm, qkv, slices, (size_t)pm.T * dm.qkvN, q_h, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN);
+        pm, qkv, slices, (size_t)pm.T * dm.qkvN, q_h, reinterpret_cast<const float2 *>(cs), kpool_layer, vpool_layer, dm.Hq, dm.Hkv, dm.D, dm.qkvN, sat);
 }
 
 // ---------------------------------------------------------------- KV import / export / synthetic fill
 // linear layout [n_pos][Hkv][D] in bf16; grid (n_pos, Hkv), block D
 __global__ void kv_io_kernel(int mode, const int *__restrict__ page_row, int first_pos, f16_t *kpool, f16_t *vpool,
-                             bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages) {
+                             bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, unsigned long long *sat) {
     int p = blockIdx.x, hd = blockIdx.y, d = threadIdx.x;
     int pos = first_pos + p;
     size_t blk = ((size_t)page_row[pos >> 4] * Hkv + hd) * (size_t)(DAS_PAGE * D);
     size_t lin = ((size_t)p * Hkv + hd) * D + d;
     int t = pos & 15;
     if (mode == 0) {
-        kpool[blk + kpage_off(t, d)] = f2h(bf2f(k_lin[lin]));
-        vpool[blk + vpage_off(t, d)] = f2h(bf2f(v_lin[lin]));
+        kpool[blk + kpage_off(t, d)] = kv_elem_counted(bf2f(k_lin[lin]), sat);
+        vpool[blk + vpage_off(t, d)] = kv_elem_counted(bf2f(v_lin[lin]), sat);
     } else {
         k_lin[lin] = f2bf(h2f(kpool[blk + kpage_off(t, d)]));
         v_lin[lin] = f2bf(h2f(vpool[blk + vpage_off(t, d)]));
     }
 }
 void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, f16_t *kpool_layer, f16_t *vpool_layer,
-                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, hipStream_t st) {
+                  bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, unsigned long long *sat, hipStream_t st) {
     if (n_pos > 0)
-        kv_io_kernel<<<dim3(n_pos, Hkv), dim3(D), 0, st>>>(mode, page_row, first_pos, kpool_layer, vpool_layer, k_lin, v_lin, Hkv, D, num_pages);
+        kv_io_kernel<<<dim3(n_pos, Hkv), dim3(D), 0, st>>>(mode, page_row, first_pos, kpool_layer, vpool_layer, k_lin, v_lin, Hkv, D, num_pages, sat);
 }
 
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {
@@ -315,6 +322,36 @@ void launch_kv_synth(const int *page_row, int ctx, f16_t *kpool_layer, f16_t *vp
     uint64_t b = host_mix64(host_mix64(seed ^ 0x4B5653594E544821ull) ^ seq_key);
     uint64_t bk = host_mix64(b ^ ((uint64_t)layer * 2u)), bv = host_mix64(b ^ ((uint64_t)layer * 2u + 1u));
     kv_synth_kernel<<<dim3(ctx, Hkv), dim3(D), 0, st>>>(page_row, kpool_layer, vpool_layer, Hkv, D, num_pages, bk, bv);
+}
+
+// ---------------------------------------------------------------- random initialisation on the device
+// Element i of a tensor is bf16(sigma * z), z = sqrt(-2 ln u1) cos(2 pi u2) in fp64, (u1, u2) from the two halves of
+// mix64(base ^ i): the counter-based generator that das.h states for das_model_load without a weight blob.
+__device__ __forceinline__ double normal_from_bits(uint64_t h) {
+    const double u1 = ((double)(uint32_t)(h >> 32) + 1.0) * (1.0 / 4294967296.0);      // (0, 1]
+    const double u2 = (double)(uint32_t)h * (1.0 / 4294967296.0);
+    return sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2);
+}
+__global__ void fill_normal_kernel(bf16_t *__restrict__ dst, size_t n, uint64_t base, double sigma) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = f2bf((float)(sigma * normal_from_bits(mix64(base ^ (uint64_t)i))));
+}
+__global__ void fill_const_kernel(bf16_t *__restrict__ dst, size_t n, bf16_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = v;
+}
+void launch_fill_normal(bf16_t *dst, size_t n, uint64_t seed, uint64_t tensor_id, double sigma, hipStream_t st) {
+    if (n == 0) return;
+    const uint64_t base = host_mix64(host_mix64(seed ^ 0x5745494748545321ull) ^ tensor_id);
+    const unsigned grid = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 64);
+    fill_normal_kernel<<<dim3(grid), dim3(256), 0, st>>>(dst, n, base, sigma);
+}
+void launch_fill_const(bf16_t *dst, size_t n, bf16_t v, hipStream_t st) {
+    if (n == 0) return;
+    const unsigned grid = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 64);
+    fill_const_kernel<<<dim3(grid), dim3(256), 0, st>>>(dst, n, v);
 }
 
 // ---------------------------------------------------------------- plain copy (counter calibration)

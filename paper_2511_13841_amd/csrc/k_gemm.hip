@@ -42,10 +42,10 @@ __device__ __forceinline__ void dma16_nt(const void *g, uint32_t lds_wave_base) 
 // 1: this workgroup walks all slices and folds each finished slice into a second set of registers;
 // 2: this workgroup computes slice blockIdx.y and stores the raw fp32 partial to slab blockIdx.y of Cv ([slices][M][ldc]).
 // PIPE: the k loop is pipelined across k-tiles and its instruction order is pinned (see k_loop_pipe).
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
-                                                             int tiles_m, int tiles_n, int slice_tiles) {
+                                                             int tiles_m, int tiles_n, int slice_tiles, int xslices) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int AB = WGM * TM, BB = WGN * TN;          // 32-row blocks per tile
     constexpr int RBU = KS * 64;                          // 16-byte units of one row block in one k-tile
@@ -61,8 +61,19 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     // XCD-aware tile order: the workgroups of one XCD (id % 8) walk a contiguous
     // run of tiles, M fastest, so tiles sharing a weight tile share an L2.
     const int nt = tiles_m * tiles_n;
-    const int per_xcd = (nt + 7) >> 3;
-    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    int t, slice = 0;
+    if (SL == 2 && xslices > 0) {
+        // K slices over workgroups, one-dimensional grid: every XCD works on ONE slice (xslices divides 8), so the part of
+        // the activation panel that an XCD reads is 1/xslices of it and stays in that XCD's L2 while the weights of the
+        // slice stream past it once
+        const int xcd = blockIdx.x & 7, per = 8 / xslices;
+        slice = xcd % xslices;
+        t = (int)(blockIdx.x >> 3) * per + xcd / xslices;
+    } else {
+        const int per_xcd = (nt + 7) >> 3;
+        t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+        if (SL == 2) slice = blockIdx.y;
+    }
     if (t >= nt) return;
     const int tile_m = t % tiles_m, tile_n = t / tiles_m;
 
@@ -70,9 +81,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int wm = wave / WGN, wn = wave % WGN;
     const int KF = K >> 4;                                 // fragments per row block
     const int KT = K / (16 * KS);                          // k-tiles
-    const int kt_begin = SL == 2 ? (int)blockIdx.y * slice_tiles : 0;
+    const int kt_begin = SL == 2 ? slice * slice_tiles : 0;
     const int kt_end = SL == 2 ? min(KT, kt_begin + slice_tiles) : KT;
-    if (SL == 2) Cv = reinterpret_cast<float *>(Cv) + (size_t)blockIdx.y * M * ldc;
+    if (SL == 2) Cv = reinterpret_cast<float *>(Cv) + (size_t)slice * M * ldc;
     const uint4 *Ag = reinterpret_cast<const uint4 *>(A);
     const uint4 *Wg = reinterpret_cast<const uint4 *>(W);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem + wave * 1024;
@@ -100,10 +111,17 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     // exactly one workgroup.  Its weight copies carry the non-temporal hint, so that the stream does not push the
     // activation panel, which all workgroups share, out of L2 (decoding a batch of 64: 63.6 -> 61.0 us per layer).  A
     // compile-time choice: decided at run time in every kernel, the branch cost the many-row narrow GEMMs 4 %.
-    constexpr bool W_ONCE = EPI == EPI_SILU_FRAG && AB == 2 && !PIPE && (A_UNITS % NT) == 0;
+    // The same holds for every launch whose workgroups own ALL rows of the pass (one wave row, three or more row blocks
+    // per wave: the few-row shapes): a weight tile is read by exactly one workgroup.
+    constexpr bool W_ONCE = (EPI == EPI_SILU_FRAG && AB == 2 && !PIPE && (A_UNITS % NT) == 0) || (WGM == 1 && TM >= 3 && WNT);
+    // (whether copy j of this wave is a weight copy is the same for all its lanes: the boundary is a multiple of 64)
+    uint32_t wmask = 0;
+#pragma unroll
+    for (int j = 0; j < NLOAD; ++j) wmask |= (uint32_t)(wave * 64 + j * NT >= A_UNITS) << j;
+    wmask = __builtin_amdgcn_readfirstlane(wmask);
     auto copy = [&](int j, int kt, int stage) {
         const uint32_t dst = (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES : lds_base + stage * STAGE_BYTES + j * NT * 16;
-        if (W_ONCE && j * NT >= A_UNITS) dma16_nt(src[j] + (size_t)kt * RBU, dst);
+        if (W_ONCE && ((wmask >> j) & 1)) dma16_nt(src[j] + (size_t)kt * RBU, dst);
         else dma16(src[j] + (size_t)kt * RBU, dst);
     };
     auto issue = [&](int kt, int stage) {                  // KS fragments = RBU uint4 per k-tile and row block
@@ -225,10 +243,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
             if (r < TNV) b[buf][r] = *reinterpret_cast<const bf16x8 *>(cur + AB * KS * 1024 + ((cb0 + r) * KS + ks) * 1024 + lane * 16);
             else a[buf][r - TNV] = *reinterpret_cast<const bf16x8 *>(cur + ((rb0 + r - TNV) * KS + ks) * 1024 + lane * 16);
         };
-        auto copy_one = [&](int kt, int stg, int j) {
-            dma16(src[j] + (size_t)kt * RBU, (j == NLOAD - 1 && surplus) ? lds_base + NS * STAGE_BYTES
-                                                                         : lds_base + stg * STAGE_BYTES + j * NT * 16);
-        };
+        auto copy_one = [&](int kt, int stg, int j) { copy(j, kt, stg); };
         int stage = 0, in_slice = 0;
         __builtin_amdgcn_s_waitcnt(0xF70 | ((NS - 2) * NLOAD & 15) | (((NS - 2) * NLOAD >> 4) << 14));
         __builtin_amdgcn_s_barrier();          // the first tile is there
@@ -392,21 +407,26 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     }
 }
 
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                       int slice_tiles = 0, int slices = 1) {
+                       int slice_tiles = 0, int slices = 1, bool slice_per_xcd = false) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
     static bool configured = false;
-    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD, SL, PIPE>;
+    auto kern = gemm_kernel<WGM, WGN, TM, TN, NS, EPI, KS, SPREAD, SL, PIPE, WNT>;
     if (!configured) {      // dynamic LDS above the default limit has to be granted once per kernel
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    if (SL == 2 && slice_per_xcd && slices >= 2 && (8 % slices) == 0) {
+        const int grid = ((tiles_m * tiles_n * slices + 7) / 8) * 8;
+        kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, slices);
+        return;
+    }
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    kern<<<dim3(grid, SL == 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles);
+    kern<<<dim3(grid, SL == 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, 0);
 }
 
 // Sum of the slice partials in ascending order, then the epilogue.  ws: [slices][MN] fp32; MN % 4 == 0.
@@ -473,6 +493,7 @@ static int cu_count() {
     }
     return n_cu;
 }
+
 
 // A must be allocated for M rounded up to 256 rows plus another 256 (tiles of 96, 192 or 288 rows read past a multiple
 // of 256), W for N rounded up to 256 rows; K % 64 == 0.
@@ -558,7 +579,20 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     // few rows: slices over workgroups when the tile grid alone would not fill the chip or K is long
     const bool few_tiles = M <= 64 || ((M + 127) / 128) * ((N + 63) / 64) < 200 || K >= 8192;
     if (M <= 512 && few_tiles && ws && ldc == N && (N % 4) == 0 && ws_floats >= mn * slices) {
+        const int MB = (M + 31) / 32;
         if (M <= 64) launch_one<1, 2, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 2>(A, W, ws, M, N, K, N, st, slice_tiles, slices);
+        else if (K >= 8192 && MB >= 5 && MB <= 10 && ((N + 127) / 128) * slices >= 128) {
+            // Long K, 129 .. 320 rows, enough (column tile, slice) pairs to fill the chip (the 7B down projection): ONE
+            // workgroup owns all rows of the pass for its 128 columns, so a weight byte is copied into LDS once instead of
+            // once per M tile (non-temporal: nobody else reads it), k-tiles of 32 in a five-stage ring; every XCD works on
+            // one K slice, whose share of the activation panel stays in its L2.  Measured at 272 rows: 84 -> 65 us
+            // (160 rows: 61 -> 48); shorter K or fewer columns leave too few workgroups and are slower this way.
+            switch (MB) {
+#define ROWS_ALL(mb) case mb: launch_one<1, 4, mb, 1, 5, EPI_F32_ROWMAJOR, 2, true, 2, false, true>(A, W, ws, M, N, K, N, st, 2 * slice_tiles, slices, true); break;
+            ROWS_ALL(5) ROWS_ALL(6) ROWS_ALL(7) ROWS_ALL(8) ROWS_ALL(9) ROWS_ALL(10)
+#undef ROWS_ALL
+            }
+        }
         else if (K >= 8192)      // long K (down projection): 128x128 tiles, k-tiles of 32 in an eight-stage ring (measured 13% faster)
             launch_one<2, 4, 2, 1, 8, EPI_F32_ROWMAJOR, 2, true, 2>(A, W, ws, M, N, K, N, st, 2 * slice_tiles, slices);
         else launch_one<2, 2, 2, 1, 3, EPI_F32_ROWMAJOR, 4, true, 2>(A, W, ws, M, N, K, N, st, slice_tiles, slices);

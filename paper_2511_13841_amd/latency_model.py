@@ -39,6 +39,42 @@ def expected_emitted(p, k, vocab):
     return (1.0 - q ** (k + 1)) / (1.0 - q)
 
 
+def sweep(workload="c3", ks=(0, 1, 2, 4, 8, 16, 32), steps=5, warmup=1, layers=None, accept_p=None, batch=None):
+    """Measure verify steps at uniform chain lengths `ks` on the workload's contexts, fit Eq. 1, and convert the measured
+    times into emitted tokens/s for a drafter of acceptance p.  Returns the report (a JSON-able dict)."""
+    ks = [int(k) for k in ks]
+    wl = di.WORKLOADS[workload]
+    p = wl.accept_p if accept_p is None else accept_p
+    ro = Rollout(dataclasses.replace(wl, mode="greedy"), batch=batch, n_layers=layers, kmax=max(ks),
+                 max_steps=(steps + warmup) * len(ks) + 2)
+    ro.random_proposals()
+    rows = []
+    for k in ks:
+        ro.wl = dataclasses.replace(ro.wl, budgets=f"k{k}")
+        for _ in range(warmup):
+            ro.step()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ro.step()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        n_toks = ro.B * (k + 1)
+        e = expected_emitted(p, k, ro.shape.vocab)
+        rows.append({"k": k, "n_toks": n_toks, "ms_per_step": ms, "expected_emitted_per_seq": e,
+                     "emitted_tokens_per_s": ro.B * e / (ms * 1e-3)})
+        log(f"[latency] k={k:2d} n_toks={n_toks:5d} {ms:8.3f} ms/step  -> {rows[-1]['emitted_tokens_per_s']:.0f} tok/s at p={p}")
+    c_base, c_tok, r2 = fit_line([r["n_toks"] for r in rows], [r["ms_per_step"] for r in rows])
+    pred = [c_base + c_tok * r["n_toks"] for r in rows]
+    best = max(rows, key=lambda r: r["emitted_tokens_per_s"])
+    out = {"workload": workload, "model": wl.model, "batch": ro.B, "kv_tokens": int(ro.ctx0.sum()),
+           "n_layers": ro.shape.n_layers, "accept_p": p,
+           "fit": {"c_base_ms": c_base, "c_tok_ms": c_tok, "r2": r2, "model": "t_fwd = c_base + c_tok * n_toks",
+                   "mean_relative_error": float(sum(abs(q - r["ms_per_step"]) / r["ms_per_step"] for q, r in zip(pred, rows)) / len(rows))},
+           "sweep": rows, "best_k": best["k"],
+           "over_proposing_hurts": bool(rows[-1]["emitted_tokens_per_s"] < best["emitted_tokens_per_s"])}
+    ro.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="c3")
@@ -46,37 +82,10 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--accept-p", type=float, default=None)
     a = ap.parse_args()
-    ks = [int(x) for x in a.ks.split(",")]
-    wl = di.WORKLOADS[a.workload]
-    p = wl.accept_p if a.accept_p is None else a.accept_p
-    ro = Rollout(dataclasses.replace(wl, mode="greedy"), n_layers=a.layers, kmax=max(ks),
-                 max_steps=(a.steps + a.warmup) * len(ks) + 2)
-    ro.random_proposals()
-    rows = []
-    for k in ks:
-        ro.wl = dataclasses.replace(ro.wl, budgets=f"k{k}")
-        for _ in range(a.warmup):
-            ro.step()
-        t0 = time.perf_counter()
-        for _ in range(a.steps):
-            ro.step()
-        ms = (time.perf_counter() - t0) / a.steps * 1e3
-        n_toks = ro.B * (k + 1)
-        e = expected_emitted(p, k, ro.shape.vocab)
-        rows.append({"k": k, "n_toks": n_toks, "ms_per_step": ms, "expected_emitted_per_seq": e,
-                     "emitted_tokens_per_s": ro.B * e / (ms * 1e-3)})
-        log(f"[latency] k={k:2d} n_toks={n_toks:5d} {ms:8.3f} ms/step  -> {rows[-1]['emitted_tokens_per_s']:.0f} tok/s at p={p}")
-    c_base, c_tok, r2 = fit_line([r["n_toks"] for r in rows], [r["ms_per_step"] for r in rows])
-    best = max(rows, key=lambda r: r["emitted_tokens_per_s"])
-    out = {"workload": a.workload, "model": wl.model, "batch": ro.B, "kv_tokens": int(ro.ctx0.sum()),
-           "n_layers": ro.shape.n_layers, "accept_p": p,
-           "fit": {"c_base_ms": c_base, "c_tok_ms": c_tok, "r2": r2, "model": "t_fwd = c_base + c_tok * n_toks"},
-           "sweep": rows, "best_k": best["k"],
-           "over_proposing_hurts": bool(rows[-1]["emitted_tokens_per_s"] < best["emitted_tokens_per_s"])}
-    print(json.dumps(out))
-    ro.dm.free()
+    print(json.dumps(sweep(a.workload, [int(x) for x in a.ks.split(",")], a.steps, a.warmup, a.layers, a.accept_p, a.batch)))
 
 
 if __name__ == "__main__":

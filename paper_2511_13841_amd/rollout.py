@@ -35,13 +35,13 @@ class Rollout:
         pages = int(sum(-(-(int(c) + grow) // 16) for c in self.ctx0)) + 64
         max_ctx = -(-(int(self.ctx0.max()) + grow + 16) // 16) * 16
         max_rows = max(self.B * (self.kmax + 1), 256)
-        t0 = time.time()
-        self.blob = di.weights_bf16(shape, seed=0)
-        log(f"[rollout] weights {self.blob.size * 2 / 1e9:.2f} GB generated in {time.time() - t0:.1f}s")
+        # random-init weights N(0, 0.02^2) from seed 0, drawn on the device by the library (the same values as
+        # das_inputs.weights_bf16(shape, 0), which is generated on the host only if somebody asks for `blob`)
+        self._blob = None
         t0 = time.time()
         self.dm = das.DasModel(das.config_for(shape, max_seqs=self.B, max_ctx=max_ctx, max_rows=max_rows,
-                                              max_draft=self.kmax, num_pages=pages), self.blob)
-        log(f"[rollout] model loaded in {time.time() - t0:.1f}s; KV pool {pages} pages "
+                                              max_draft=self.kmax, num_pages=pages), None, seed=0)
+        log(f"[rollout] model initialised and packed on the device in {time.time() - t0:.1f}s; KV pool {pages} pages "
             f"({pages * 16 * shape.kv_bytes_per_token / 1e9:.1f} GB)")
         self.ids = list(range(self.B))
         rng = np.random.default_rng(self.seed + 17)
@@ -54,12 +54,26 @@ class Rollout:
             for i in self.ids:
                 self.dm.seq_create(i, int(self.ctx0[i]), int(self.pending0[i]))
                 self.dm.kv_synth(i, self.seed, i)
-        log(f"[rollout] contexts ({context}): {int(self.ctx0.sum())} tokens in {time.time() - t0:.1f}s")
+        self.context_s = time.time() - t0
+        log(f"[rollout] contexts ({context}): {int(self.ctx0.sum())} tokens in {self.context_s:.1f}s")
         self.ctx = self.ctx0.copy()
         self.pending = self.pending0.copy()
         self.future = None
         self.faithful = False
         self.rollback = False            # time the verify pass alone: every step is rolled back instead of committed
+
+    @property
+    def blob(self):
+        """The canonical weight blob of the same model on the host (for a CPU baseline)."""
+        if self._blob is None:
+            t0 = time.time()
+            self._blob = di.weights_bf16(self.shape, seed=0)
+            log(f"[rollout] host copy of the weights ({self._blob.size * 2 / 1e9:.2f} GB) generated in {time.time() - t0:.1f}s")
+        return self._blob
+
+    def close(self):
+        self.dm.free()
+        self._blob = None
 
     def generate_trajectories(self):
         """Plain decoding (k=0 verify steps) for `horizon` tokens, then rewind.  future[i][0] is the pending token."""

@@ -117,7 +117,9 @@ def solver_budgets(lens, c_base, c_tok, alpha, cap, k_max):
 
 
 def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, ctx_lo=256, ctx_hi=1024, seed=4000,
-        n_layers=None, policy="classes", c_base=8.0, c_tok=0.017, alpha=0.6, cap=0.9, drafter="synthetic"):
+        n_layers=None, policy="classes", c_base=8.0, c_tok=0.017, alpha=0.6, cap=0.9, drafter="synthetic", keep_rollouts=False):
+    """keep_rollouts: also return, under "rollouts", what a checker needs to replay the batch elsewhere: the context
+    lengths, the first pending tokens, the seed of the synthetic KV (sequence i has key i) and both token streams."""
     shape = di.MODELS[model]
     if n_layers is not None:
         shape = shape.replace(n_layers=n_layers)
@@ -132,9 +134,8 @@ def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, c
     kmax = int(max(k_medium, k_long, 1))
     room = int(max_len) + kmax + 4
     pages = int(sum(-(-(int(c) + room) // 16) for c in ctx0)) + 16
-    blob = di.weights_bf16(shape, seed=0)
     dm = das.DasModel(das.config_for(shape, max_seqs=batch, max_ctx=-(-(int(ctx0.max()) + room + 16) // 16) * 16,
-                                     max_rows=max(batch * (kmax + 1), 256), max_draft=kmax, num_pages=pages), blob)
+                                     max_rows=max(batch * (kmax + 1), 256), max_draft=kmax, num_pages=pages), None, seed=0)
     ids = list(range(batch))
     pend0 = rng.integers(0, shape.vocab, size=batch, dtype=np.int32)
     for i in ids:
@@ -161,7 +162,8 @@ def run(model="7b", batch=64, max_len=512, accept_p=0.7, k_medium=4, k_long=8, c
     mismatched = sum(int(not np.array_equal(out[i], traj[i])) for i in ids)
     dm.free()
     half = next((r for r, n in enumerate(hist) if n <= batch // 2), len(hist))
-    return {"model": model, "n_layers": shape.n_layers, "batch": batch, "drafter": drafter,
+    extra = {"rollouts": {"ctx0": ctx0, "pend0": pend0, "kv_seed": seed, "plain": traj, "speculative": out}} if keep_rollouts else {}
+    return {**extra, "model": model, "n_layers": shape.n_layers, "batch": batch, "drafter": drafter,
             "accept_p": accept_p if drafter == "synthetic" else None,
             "policy": policy, "budgets": {"short": 0, "medium": k_medium, "long": k_long} if policy == "classes" else
             {"k_max": kmax, "mean_k": float(np.mean(budgets)), "sequences_without_speculation": int((budgets == 0).sum()),

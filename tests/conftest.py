@@ -7,8 +7,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+_capture_manager = None
+
+
 def pytest_configure(config):
+    global _capture_manager
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    _capture_manager = config.pluginmanager.getplugin("capturemanager")
+
+
+def progress(*args):
+    """A line that reaches the terminal while the test is still running, whatever pytest's capture mode: the long GPU
+    tests (oracle on the host for minutes) report each step, so that a watcher can tell a slow test from a hung one."""
+    line = " ".join(str(a) for a in args)
+    if _capture_manager is not None:
+        with _capture_manager.global_and_fixture_disabled():
+            print("\n[progress] " + line, end="", file=sys.stderr, flush=True)
+    else:
+        print(line, file=sys.stderr, flush=True)
 
 
 @pytest.fixture(scope="session")

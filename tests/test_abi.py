@@ -35,13 +35,13 @@ def test_error_paths_without_a_gpu_or_model():
     assert L.das_kv_commit(None, 1, None, None, None) == das.DAS_ERR_INVALID
     assert L.das_kv_rollback(None, 0, None) == das.DAS_ERR_INVALID
     h = ctypes.c_void_p()
-    assert L.das_model_load(None, None, None, ctypes.byref(h)) == das.DAS_ERR_INVALID
+    assert L.das_model_load(None, 0, None, None, ctypes.byref(h)) == das.DAS_ERR_INVALID
     import das_inputs as di
     bad = das.config_for(di.MODELS["tiny"], 8, 1024, 64, 200, 64)        # (1+max_draft)*G > 256
     dummy = (ctypes.c_uint16 * 4)()
-    assert L.das_model_load(ctypes.byref(bad), dummy, None, ctypes.byref(h)) == das.DAS_ERR_INVALID
+    assert L.das_model_load(ctypes.byref(bad), 0, dummy, None, ctypes.byref(h)) == das.DAS_ERR_INVALID
     bad = das.config_for(di.MODELS["tiny"].replace(head_dim=96), 8, 1024, 64, 4, 64)
-    assert L.das_model_load(ctypes.byref(bad), dummy, None, ctypes.byref(h)) == das.DAS_ERR_INVALID
+    assert L.das_model_load(ctypes.byref(bad), 0, dummy, None, ctypes.byref(h)) == das.DAS_ERR_INVALID
     assert "attention" in das.kernel_classes()
 
 

@@ -15,7 +15,8 @@ def das():
 
 @pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256), (520, 16512, 192), (257, 16384, 64), (560, 16640, 192),
                                    (40, 320, 1024), (300, 256, 3584), (530, 192, 3136), (64, 128, 16448), (513, 96, 16384),
-                                   (600, 16384, 64), (1030, 16448, 320), (320, 16400, 128), (450, 16384, 192)])
+                                   (600, 16384, 64), (1030, 16448, 320), (320, 16400, 128), (450, 16384, 192),
+                                   (272, 2048, 16384), (160, 2176, 16448), (230, 2048, 16384)])
 def test_mfma_gemm_against_fp64(das, M, N, K):
     rng = np.random.default_rng(M * 7 + N)
     a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
@@ -72,7 +73,7 @@ def test_row_maximum_epilogue_against_fp64(das, M, N, K):
     assert np.all(ref[open_rows, got[open_rows]] >= ref[open_rows].max(axis=1) - 1e-4 * np.sqrt(K) * np.abs(ref).max())
 
 
-@pytest.mark.parametrize("N,K", [(320, 3584), (192, 18944), (16416, 1024), (256, 960)])
+@pytest.mark.parametrize("N,K", [(320, 3584), (192, 18944), (16416, 1024), (256, 960), (2048, 16384)])
 def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K):
     """A row of the product is the same bits whether it is computed among 7, 70, 300 or 600 rows: narrow outputs sum
     K in slices whose layout depends on K alone, whichever kernel shape (slices over workgroups, or folded in
@@ -81,7 +82,7 @@ def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K):
     a = di.f32_to_bf16(rng.standard_normal((600, K)).astype(np.float32))
     w = di.f32_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
     full = das.debug_gemm(a, w)
-    for m in (7, 70, 300, 520):
+    for m in (7, 70, 150, 300, 520):      # (N = 2048, K = 16384 at 150 and 300 rows: all rows in one workgroup per column tile)
         print(f"gemm rows {m} of 600, N={N} K={K}", flush=True)
         part = das.debug_gemm(a[:m], w)
         assert np.array_equal(part, full[:m]), (m, float(np.abs(part - full[:m]).max()))
@@ -135,4 +136,60 @@ def test_kv_synth_import_export_are_bit_exact(das, model):
     assert list(got[:4]) == [65536.0, -65536.0, 65280.0, 2.0 ** -17], got
     assert abs(got[4] - 1.0e-6) <= 3.0e-8 and got[5] == 0.0, got
     np.testing.assert_array_equal(k, v)
+    dm.free()
+
+
+def test_device_random_init_equals_the_host_blob(das):
+    """das_model_load without a weight blob draws the N(0, 0.02^2) weights on the device from the seed with the same
+    counter-based generator as das_inputs.weights_bf16: a model loaded either way gives the same bits (logits of a
+    prefill and of a verify step, written KV)."""
+    for shape in (di.MODELS["tiny"], di.MODELS["tiny"].replace(n_q_heads=6, n_kv_heads=2, head_dim=128, d_model=384, d_ffn=1000, vocab=20000)):
+        cfg = das.config_for(shape, max_seqs=4, max_ctx=256, max_rows=64, max_draft=4, num_pages=64)
+        prompts = di.prompts([19, 40], shape.vocab, 5)
+        got = []
+        for blob in (di.weights_bf16(shape, seed=3), None):
+            dm = das.DasModel(cfg, blob, keep_logits=True, seed=3)
+            nxt = dm.prefill([0, 1], prompts)
+            l0 = dm.debug_logits()
+            acc, nx = dm.verify_step([0, 1], [19, 40], [[5, 6, 7], [8]])
+            got.append((nxt, l0, acc, nx, dm.debug_logits(), dm.kv_export(1, shape.n_layers - 1, 0, 41)))
+            dm.free()
+        a, b = got
+        for x, y in zip(a[:5], b[:5]):
+            assert np.array_equal(x, y)
+        assert np.array_equal(a[5][0], b[5][0]) and np.array_equal(a[5][1], b[5][1])
+    # a different seed is a different model
+    dm = das.DasModel(cfg, None, keep_logits=True, seed=4)
+    dm.prefill([0, 1], prompts)
+    assert not np.array_equal(dm.debug_logits(), got[1][1])
+    dm.free()
+
+
+def test_kv_saturation_is_counted(das):
+    """K/V pages hold bf16 values in binary16 containers: a value beyond +-65504 is stored saturated, and every such
+    store is counted where the caller can read it -- from das_kv_import and from a pass that computes such values."""
+    shape = di.MODELS["tiny"]
+    blob = di.weights_bf16(shape, seed=0)
+    cfg = das.config_for(shape, max_seqs=4, max_ctx=256, max_rows=64, max_draft=4, num_pages=64)
+    dm = das.DasModel(cfg, blob)
+    prompts = di.prompts([30], shape.vocab, 1)
+    dm.prefill([0], prompts)
+    dm.verify_step([0], [30], [[1, 2]])
+    dm.kv_commit([0], [0], [7])
+    assert dm.debug_kv_saturated() == 0
+    k = np.zeros((3, shape.n_kv_heads, shape.head_dim), np.float32)
+    v = np.zeros_like(k)
+    k[0, 0, :2] = [70000.0, -1.0e9]
+    v[2, 1, 5] = 3.0e38
+    k[1, 0, 0] = 65280.0                                   # the largest bf16 below the container's maximum: not counted
+    dm.kv_import(0, 1, 4, di.f32_to_bf16(k), di.f32_to_bf16(v))
+    assert dm.debug_kv_saturated() == 3
+    dm.free()
+    # a model whose first input gain is 1e7 produces keys and values of the order 1e6 in layer 0
+    hot = blob.copy()
+    off = shape.vocab * shape.d_model
+    hot[off:off + shape.d_model] = di.f32_to_bf16(np.full(shape.d_model, 1.0e7, np.float32))
+    dm = das.DasModel(cfg, hot)
+    dm.prefill([0], prompts)
+    assert dm.debug_kv_saturated() > 100
     dm.free()
