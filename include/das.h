@@ -169,6 +169,17 @@ int das_debug_kv_saturated(das_model *m, int64_t *count);
 /* Stand-alone run of the MFMA GEMM kernel the projections use: c[M][N] (fp32) = a[M][K] * w[N][K]^T,
  * a and w row-major bf16, K a multiple of 8.  Needs no model. */
 int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a, const uint16_t *w, float *c);
+/* das_debug_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  c_dev[M][N] (fp32) = a_dev[M][K] * w_dev[N][K]^T with a_dev, w_dev row-major bf16 and
+ * c_dev all DEVICE pointers owned by the caller (valid on the current device).  Calls no hipMalloc / hipFree and no
+ * allocating library routine: the repacked operands and the K-slice partial sums live in a 14 MiB array that the library
+ * keeps on every GPU it runs on until the process ends.  Limits: M <= 256, N <= 2048, K <= 2048 (K a multiple of 8);
+ * anything larger is DAS_ERR_INVALID with a message in das_last_device_error().  The kernels are enqueued on
+ * `hip_stream` (NULL: the default stream) and the call returns WITHOUT synchronising: c_dev is complete when the
+ * stream reaches this point.  All calls on one GPU share that GPU's array: calls that overlap on one GPU (different
+ * streams, different threads) race; calls on one stream are ordered.  Same kernels, same bits as das_debug_gemm. */
+int das_gemm_noalloc(int32_t M, int32_t N, int32_t K, const uint16_t *a_dev, const uint16_t *w_dev, float *c_dev,
+                     void *hip_stream);
 /* The same kernel with its other two epilogues, on row-major bf16 host inputs a[M][K] (K a multiple of 64):
  * act[M][F] (host, fp32 values of the bf16 the kernel stores) = silu(a wg^T) * (a wu^T) with wg, wu [F][K], F a
  * multiple of 8 -- the gate/up projection (Sec. 3 names the model families; SwiGLU FFN);

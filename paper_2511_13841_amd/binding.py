@@ -68,6 +68,7 @@ def lib():
             "das_debug_gemm_time": [I, I, I, I, I, I, C.POINTER(C.c_double)],
             "das_debug_gemm": [I, I, I, VP, VP, VP],
             "das_debug_gemm_epilogues": [I, I, VP, I, VP, VP, VP, I, VP, VP],
+            "das_gemm_noalloc": [I, I, I, VP, VP, VP, VP],
             "das_debug_copy": [C.c_int64, I],
             "das_profile_enable": [P, I],
             "das_profile_reset": [P],
@@ -122,6 +123,12 @@ def debug_gemm(a_bf16, w_bf16):
     c = np.empty((M, N), np.float32)
     _chk(lib().das_debug_gemm(M, N, K, a.ctypes.data, w.ctypes.data, c.ctypes.data), "das_debug_gemm")
     return c
+
+
+def gemm_noalloc(M, N, K, a_dev, w_dev, c_dev, stream=None):
+    """das_gemm_noalloc on raw device addresses (ints): enqueues on `stream`, does not synchronise, allocates nothing."""
+    _chk(lib().das_gemm_noalloc(int(M), int(N), int(K), C.c_void_p(int(a_dev)), C.c_void_p(int(w_dev)), C.c_void_p(int(c_dev)),
+                                C.c_void_p(int(stream or 0))), "das_gemm_noalloc")
 
 
 def debug_gemm_silu(a_bf16, wg_bf16, wu_bf16):

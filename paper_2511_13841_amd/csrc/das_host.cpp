@@ -954,6 +954,58 @@ extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a
     return rc;
 }
 
+// ------------------------------------------------------------------------------------------------ no-allocation GEMM
+// das_debug_gemm for callers that cannot allocate: operands and result are DEVICE pointers, and everything the kernels
+// need beyond them (both operands repacked into fragment order, the K-slice partial sums) lives in one file-scope
+// device array.  Each GPU holds its own copy of the array at its own address; the address is asked for once per
+// device and only that pointer, never the array's name, is handed to kernels.
+#define DAS_NOALLOC_MAX_M 256
+#define DAS_NOALLOC_MAX_N 2048
+#define DAS_NOALLOC_MAX_K 2048
+#define DAS_NOALLOC_PA_BYTES ((size_t)(DAS_NOALLOC_MAX_M + 256) * DAS_NOALLOC_MAX_K * 2)                 /* 2 MiB */
+#define DAS_NOALLOC_PW_BYTES ((size_t)DAS_NOALLOC_MAX_N * DAS_NOALLOC_MAX_K * 2)                         /* 8 MiB */
+#define DAS_NOALLOC_WS_BYTES ((size_t)2 * DAS_NOALLOC_MAX_M * DAS_NOALLOC_MAX_N * 4)                     /* 4 MiB: at most two K slices */
+static __device__ __align__(256) unsigned char scratch[DAS_NOALLOC_PA_BYTES + DAS_NOALLOC_PW_BYTES + DAS_NOALLOC_WS_BYTES];
+#define DAS_NOALLOC_MAX_DEVICES 64
+static unsigned char *g_scratch_ptr[DAS_NOALLOC_MAX_DEVICES];      // device address of `scratch` on each GPU, filled on first use
+
+extern "C" int das_gemm_noalloc(int32_t M, int32_t N, int32_t K, const uint16_t *a_dev, const uint16_t *w_dev, float *c_dev,
+                                void *hip_stream) {
+    if (M < 1 || N < 1 || K < 8 || (K % 8) || !a_dev || !w_dev || !c_dev) return DAS_ERR_INVALID;
+    if (M > DAS_NOALLOC_MAX_M || N > DAS_NOALLOC_MAX_N || K > DAS_NOALLOC_MAX_K) {
+        g_dev_err = "das_gemm_noalloc: at most 256 x 2048 x 2048 (M x N x K); larger products need das_debug_gemm";
+        return DAS_ERR_INVALID;
+    }
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= DAS_NOALLOC_MAX_DEVICES) { g_dev_err = "das_gemm_noalloc: device index out of range"; return DAS_ERR_DEVICE; }
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { g_dev_err = "das_gemm_noalloc: no device address for the scratch array"; return DAS_ERR_DEVICE; }
+        g_scratch_ptr[dev] = reinterpret_cast<unsigned char *>(p);
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int Mp = round_up(M, 256) + 256, Np = round_up(N, 256), Kp = round_up(K, 64);
+    unsigned char *base = g_scratch_ptr[dev];
+    bf16_t *pa = reinterpret_cast<bf16_t *>(base);
+    bf16_t *pw = reinterpret_cast<bf16_t *>(base + DAS_NOALLOC_PA_BYTES);
+    float *ws = reinterpret_cast<float *>(base + DAS_NOALLOC_PA_BYTES + DAS_NOALLOC_PW_BYTES);
+    int slice_tiles = 0;
+    const int slices = gemm_slices(Kp, &slice_tiles);
+    const size_t ws_floats = (size_t)slices * M * N;
+    if ((size_t)Mp * Kp * 2 > DAS_NOALLOC_PA_BYTES || (size_t)Np * Kp * 2 > DAS_NOALLOC_PW_BYTES || ws_floats * 4 > DAS_NOALLOC_WS_BYTES)
+        return DAS_ERR_INVALID;      // (cannot happen inside the limits above)
+    // the repacking kernels write every 16-byte slot of their padded outputs, zeros included, and the GEMM writes every
+    // partial it later reads: nothing of the previous call's contents survives where it could be read
+    launch_pack_weight(a_dev, pa, M, K, Mp, Kp, st);
+    launch_pack_weight(w_dev, pw, N, K, Np, Kp, st);
+    launch_gemm(EPI_F32_ROWMAJOR, pa, pw, c_dev, M, N, Kp, N, st, ws, ws_floats);
+    hipError_t le = hipGetLastError();
+    if (le != hipSuccess) { g_dev_err = std::string("das_gemm_noalloc launch: ") + hipGetErrorString(le); return DAS_ERR_DEVICE; }
+    return DAS_OK;
+}
+
 // Stand-alone check of the GEMM's other two epilogues, from row-major bf16 host inputs:
 //   act[M][F] = silu(a wg^T) * (a wu^T), rounded to bf16 as the kernel writes it, returned as fp32 (wg, wu: [F][K]);
 //   col[M]    = lowest column of the row maximum of a w^T (w: [N][K], N >= 16384: the fused LM head).
