@@ -80,6 +80,8 @@ struct das_model {
     bool keep_logits = false;        // materialise fp32 logits of every greedy pass (inspection); sampling always does
     bool last_has_logits = false, last_has_argmax = false;
     unsigned long long *d_keys = nullptr;   // (row maximum, ~column) keys gathered by the LM-head GEMM
+    // sampling passes: per-block softmax statistics [ceil(V/32)][max_rows] (m_b, z_b), then max_rows draft logits
+    float2 *stat_part = nullptr;
     // profiling
     bool prof = false;
     struct Ev { int cls; hipEvent_t a, b; };
@@ -163,7 +165,7 @@ static PassSize pass_size(const das_model *m, const std::vector<PassBlock> &bloc
         T += b.n; items += nchunk; prow += nchunk * nrb;
         if (nchunk > 1) mblk += nrb;
     }
-    return {4 * T + 6 * blocks.size() + 2 * items * m->dm.Hkv + 2 * mblk + 2 * n_upd + 2 * n_u, prow};
+    return {5 * T + 6 * blocks.size() + 2 * items * m->dm.Hkv + 2 * mblk + 2 * n_upd + 2 * n_u, prow};
 }
 static int check_pass_size(const das_model *m, const PassSize &ps) {
     if (ps.stage_ints > m->stage_ints) return DAS_ERR_INVALID;        // over a configured maximum
@@ -175,8 +177,10 @@ static int check_pass_size(const das_model *m, const PassSize &ps) {
 // Rows of all blocks go through the layer stack; logits (+ argmax) are produced for the
 // selected rows.  On return kernels are enqueued, nothing is synchronised.  The caller has checked pass_size() against
 // the staging block and the partial buffers: nothing here allocates.
+// inv_temp > 0: a sampling pass (1 / temperature): the logits' per-block softmax statistics and every row's draft logit
+// are produced (m->stat_part), and the row statistics (m->row_stats); u_sample is then non-null.
 static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const float *u_accept, const float *u_sample,
-                    int n_u, PassMeta *pm_out, const float **d_ua, const float **d_us) {
+                    int n_u, float inv_temp, PassMeta *pm_out, const float **d_ua, const float **d_us) {
     const DasDims &dm = m->dm;
     const int NB = (int)blocks.size();
     int T = 0;
@@ -189,6 +193,7 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
     int *row_pos = p; p += T;
     int *row_b = p; p += T;
     int *sel = p; p += T;
+    int *dtok = p; p += T;         // per selected row: the draft token its logits are tested against (-1: none)
     int *b_slot = p; p += NB;
     int *b_start = p; p += NB;
     int *b_n = p; p += NB;
@@ -212,7 +217,10 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         for (int c = 0; c < nchunk; ++c) { items[cls].push_back(b); items[cls].push_back(c); }
         for (int j = 0; j < pb.n; ++j, ++r) {
             tok[r] = pb.toks[j]; row_pos[r] = pb.start + j; row_b[r] = b;
-            if (pb.want == 2 || (pb.want == 1 && j == pb.n - 1)) sel[n_sel++] = r;
+            if (pb.want == 2 || (pb.want == 1 && j == pb.n - 1)) {
+                dtok[n_sel] = (pb.want == 2 && j + 1 < pb.n) ? pb.toks[j + 1] : -1;
+                sel[n_sel++] = r;
+            }
         }
     }
     if (prow > m->part_rows_cap) return DAS_ERR_NOMEM;
@@ -296,19 +304,34 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         // Greedy passes need one number per row, the first column of the row maximum: the LM-head GEMM gathers it in
         // its epilogue and the [rows][vocab] logits never reach memory.  Sampling, inspection mode and small
         // vocabularies (narrow GEMM shapes) write the logits and scan them.
-        const bool fused = !m->keep_logits && !u_accept && !u_sample && dm.V >= 16384;
-        if (fused) {
+        const bool sampling = inv_temp > 0.f;
+        const bool fused = !m->keep_logits && !sampling && dm.V >= 16384;
+        const int nblk = (dm.V + 31) / 32, ldp = m->cfg.max_rows;
+        float *draft_logit = reinterpret_cast<float *>(m->stat_part + (size_t)nblk * ldp);
+        if (sampling && !m->keep_logits && gemm_rowstats_supported(n_sel, dm.V)) {
+            // a sampling pass does not need its logits either: the LM-head GEMM leaves per-block softmax statistics and the
+            // draft tokens' logits, and the one block a draw falls into is computed again by the kernel that draws
+            { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_ROWSTATS, m->xsel, m->wlm, m->stat_part, n_sel, dm.V, dm.d, ldp, st, m->gemm_ws, m->gemm_ws_floats, nullptr, nullptr, dptr(dtok), inv_temp); }
+            { ProfScope ps(m, KC_SAMPLE); launch_row_stats_merge(m->stat_part, ldp, dm.V, n_sel, inv_temp, reinterpret_cast<float2 *>(m->row_stats), st); }
+            m->last_has_argmax = false;
+            m->last_has_logits = false;
+        } else if (fused) {
             { ProfScope ps(m, KC_ARGMAX); launch_rowmax_keys_clear(m->d_keys, n_sel, st); }
             { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_ROWMAX, m->xsel, m->wlm, m->d_keys, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
             { ProfScope ps(m, KC_ARGMAX); launch_rowmax_keys_decode(m->d_keys, n_sel, m->d_g, st); }
         } else {
             { ProfScope ps(m, KC_GEMM_LMHEAD); launch_gemm(EPI_F32_ROWMAJOR, m->xsel, m->wlm, m->logits, n_sel, dm.V, dm.d, dm.V, st, m->gemm_ws, m->gemm_ws_floats); }
             // the row argmax is what greedy acceptance reads; a sampling pass needs it only for inspection
-            if (!(u_accept || u_sample) || m->keep_logits) { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
-            m->last_has_argmax = !(u_accept || u_sample) || m->keep_logits;
+            if (!sampling || m->keep_logits) { ProfScope ps(m, KC_ARGMAX); launch_argmax(m->logits, n_sel, dm.V, m->d_g, st); }
+            m->last_has_argmax = !sampling || m->keep_logits;
+            m->last_has_logits = true;
+            if (sampling) {
+                ProfScope ps(m, KC_SAMPLE);
+                launch_block_stats(m->logits, n_sel, dm.V, inv_temp, dptr(dtok), m->stat_part, ldp, draft_logit, st);
+                launch_row_stats_merge(m->stat_part, ldp, dm.V, n_sel, inv_temp, reinterpret_cast<float2 *>(m->row_stats), st);
+            }
         }
-        if (fused) m->last_has_argmax = true;
-        m->last_has_logits = !fused;
+        if (fused) { m->last_has_argmax = true; m->last_has_logits = false; }
     }
     hipError_t le = hipGetLastError();
     if (le != hipSuccess) { g_dev_err = std::string("kernel launch: ") + hipGetErrorString(le); return DAS_ERR_DEVICE; }
@@ -431,6 +454,7 @@ static int load_impl(das_model *m, const uint16_t *wb, uint64_t seed) {
     A(m->h, Mp * d); A(m->xn, Mp * d); A(m->qkv, Mp * dm.qkvN); A(m->q_h, Mp * qd); A(m->attn, Mp * qd); A(m->act, Mp * Fp); A(m->xsel, Mp * d);
     A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
     A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs); A(m->d_keys, (size_t)c.max_rows);
+    A(m->stat_part, (size_t)((V + 31) / 32) * c.max_rows + ((size_t)c.max_rows + 1) / 2);
     {   // slice partials of the narrow GEMMs when a pass has at most 512 rows: [slices <= 8][rows][widest narrow output]
         const size_t n_narrow = std::max<size_t>(std::max<size_t>(dm.qkvN, d), V < 16384 ? V : 0);
         m->gemm_ws_floats = 8 * std::min<size_t>(512, Mp) * n_narrow;
@@ -457,7 +481,7 @@ static int load_impl(das_model *m, const uint16_t *wb, uint64_t seed) {
     }
     // ---- staging (see pass_size)
     const size_t max_items = (size_t)m->max_blocks * (c.max_ctx / chunk_tokens + 2);
-    m->stage_ints = 6 * (size_t)c.max_rows + 6 * (size_t)m->max_blocks + 2 * max_items * dm.Hkv +
+    m->stage_ints = 7 * (size_t)c.max_rows + 6 * (size_t)m->max_blocks + 2 * max_items * dm.Hkv +
                     2 * ((size_t)c.max_rows * dm.G / 16 + (size_t)m->max_blocks) +
                     2 * ((size_t)c.max_rows / DAS_PAGE + 2 * (size_t)c.max_seqs + 2) + 64;
     HIPCHK(hipHostMalloc((void **)&m->h_stage, m->stage_ints * sizeof(int), hipHostMallocDefault));
@@ -607,14 +631,16 @@ extern "C" int das_prefill(das_model *m, int32_t n, const int32_t *seq_ids, cons
         int n_fin = 0;
         for (auto &b : blocks) n_fin += b.want ? 1 : 0;
         if (sampling && n_fin) for (size_t bi = 0; bi < blocks.size(); ++bi) if (blocks[bi].want) us.push_back(sampling->u_sample[who[bi]]);
-        rc = run_pass(m, blocks, nullptr, us.empty() ? nullptr : us.data(), (int)us.size(), &pm, &d_ua, &d_us);
+        rc = run_pass(m, blocks, nullptr, us.empty() ? nullptr : us.data(), (int)us.size(), us.empty() ? 0.f : 1.f / sampling->temperature,
+                      &pm, &d_ua, &d_us);
         if (rc != DAS_OK) break;
         if (n_fin) {
             if (sampling) {
                 ProfScope ps(m, KC_SAMPLE);
-                launch_row_stats(m->logits, n_fin, m->dm.V, 1.f / sampling->temperature, m->row_stats, m->st);
-                launch_sample(m->logits, m->dm.V, pm.tok, pm.b_row0, pm.b_n, n_fin, 1.f / sampling->temperature, nullptr, d_us, 1,
-                              m->row_stats, m->d_accept, m->d_next, m->st);
+                const int nblk = (m->dm.V + 31) / 32, ldp = m->cfg.max_rows;
+                launch_sample(m->stat_part, ldp, m->dm.V, reinterpret_cast<const float2 *>(m->row_stats),
+                              reinterpret_cast<const float *>(m->stat_part + (size_t)nblk * ldp), m->xsel, m->wlm, m->dm.d, pm.tok, pm.b_row0,
+                              pm.b_n, n_fin, 1.f / sampling->temperature, nullptr, d_us, 1, m->d_accept, m->d_next, m->st);
                 if (hipMemcpyAsync(m->h_out, m->d_next, n_fin * sizeof(int), hipMemcpyDeviceToHost, m->st) != hipSuccess) rc = DAS_ERR_DEVICE;
             } else {
                 if (hipMemcpyAsync(m->h_out, m->d_g, n_fin * sizeof(int), hipMemcpyDeviceToHost, m->st) != hipSuccess) rc = DAS_ERR_DEVICE;
@@ -693,13 +719,14 @@ extern "C" int das_verify_step(das_model *m, int32_t n, const int32_t *seq_ids, 
     PassMeta pm;
     const float *d_ua = nullptr, *d_us = nullptr;
     int rc = run_pass(m, blocks, sampling ? sampling->u_accept : nullptr, sampling ? sampling->u_sample : nullptr, (int)T,
-                      &pm, &d_ua, &d_us);
+                      sampling ? 1.f / sampling->temperature : 0.f, &pm, &d_ua, &d_us);
     if (rc == DAS_OK) {
         if (sampling) {
             ProfScope ps(m, KC_SAMPLE);
-            launch_row_stats(m->logits, (int)T, m->dm.V, 1.f / sampling->temperature, m->row_stats, m->st);
-            launch_sample(m->logits, m->dm.V, pm.tok, pm.b_row0, pm.b_n, n, 1.f / sampling->temperature, d_ua, d_us, 0,
-                          m->row_stats, m->d_accept, m->d_next, m->st);
+            const int nblk = (m->dm.V + 31) / 32, ldp = m->cfg.max_rows;
+            launch_sample(m->stat_part, ldp, m->dm.V, reinterpret_cast<const float2 *>(m->row_stats),
+                          reinterpret_cast<const float *>(m->stat_part + (size_t)nblk * ldp), m->xsel, m->wlm, m->dm.d, pm.tok, pm.b_row0,
+                          pm.b_n, n, 1.f / sampling->temperature, d_ua, d_us, 0, m->d_accept, m->d_next, m->st);
         } else {
             ProfScope ps(m, KC_ACCEPT);
             launch_accept_greedy(m->d_g, pm.b_row0, pm.b_n, pm.tok, n, m->d_accept, m->d_next, m->st);

@@ -82,7 +82,9 @@ struct PassMeta {
 
 // EPI_ROWMAX: no matrix is written; every row's (largest value, lowest column holding it) is folded into a 64-bit key per
 // row with atomic max (value in the high word as an order-preserving integer, ~column in the low word)
-enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3, EPI_ROWMAX = 4 };
+// EPI_ROWSTATS: no matrix is written either; per row and 32-column block the softmax statistics (block maximum, sum of
+// exp((l - max) / T)) and, per row, the logit of one given column (the row's draft token): what a sampling pass needs
+enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3, EPI_ROWMAX = 4, EPI_ROWSTATS = 5 };
 
 // ---- launchers (each enqueues on `st`; none synchronises) ----
 void launch_pack_weight(const bf16_t *src, bf16_t *dst, int N, int K, int Np, int Kp, hipStream_t st);
@@ -110,8 +112,12 @@ void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h
 // left_slices (EPI_F32_ROWMAJOR only): a caller whose next kernel can add the K-slice partials itself passes a pointer.
 // When the launch leaves the partials in ws ([slices][M][N], to be added in ascending order) it stores their count there
 // and C stays unwritten; otherwise it stores 1 and C holds the product.
+// EPI_ROWSTATS (only where gemm_rowstats_supported): C = float2 [ceil(N/32)][ldc] block statistics followed by float [ldc]
+// draft logits; aux_tok[row] = the column whose logit is wanted (-1: none), aux_f = 1 / temperature.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr);
+                 float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr,
+                 const int *aux_tok = nullptr, float aux_f = 0.f);
+bool gemm_rowstats_supported(int M, int N);
 int gemm_slices(int K, int *slice_tiles);
 // split-KV partial attention for the items of one row-block class, then the merge.  Sequences of one chunk are finished
 // by launch_attn itself (their rows go straight to out_frag, bit-equal to what the merge would write), so pm.mblk lists
@@ -126,10 +132,14 @@ void launch_rowmax_keys_clear(unsigned long long *keys, int n_rows, hipStream_t 
 void launch_rowmax_keys_decode(const unsigned long long *keys, int n_rows, int *out, hipStream_t st);
 void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const int *tok, int NB,
                           int *accept_len, int *next_token, hipStream_t st);
-void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, float *stats, hipStream_t st);
-void launch_sample(const float *logits, int V, const int *tok, const int *b_row0, const int *b_n, int NB,
-                   float inv_temp, const float *u_accept, const float *u_sample, int prefill_mode,
-                   float *row_stats, int *accept_len, int *next_token, hipStream_t st);
+// Stochastic acceptance on per-block softmax statistics (see k_head.hip): part = float2 [ceil(V/32)][ldp], from the LM-head
+// GEMM (EPI_ROWSTATS) or from written logits (launch_block_stats); stats = float2 [rows] (M, Z).
+void launch_block_stats(const float *logits, int n_rows, int V, float inv_temp, const int *dtok, float2 *part, int ldp,
+                        float *draft_logit, hipStream_t st);
+void launch_row_stats_merge(const float2 *part, int ldp, int V, int n_rows, float inv_temp, float2 *stats, hipStream_t st);
+void launch_sample(const float2 *part, int ldp, int V, const float2 *stats, const float *draft_logit, const bf16_t *xsel,
+                   const bf16_t *wlm, int K, const int *tok, const int *b_row0, const int *b_n, int NB, float inv_temp,
+                   const float *u_accept, const float *u_sample, int prefill_mode, int *accept_len, int *next_token, hipStream_t st);
 // k_lin / v_lin: bf16, linear [n_pos][Hkv][D]; mode 0 imports into the pages, mode 1 exports
 void launch_kv_io(int mode, const int *page_row, int first_pos, int n_pos, f16_t *kpool_layer, f16_t *vpool_layer,
                   bf16_t *k_lin, bf16_t *v_lin, int Hkv, int D, int num_pages, unsigned long long *sat, hipStream_t st);

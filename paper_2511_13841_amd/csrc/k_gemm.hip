@@ -45,7 +45,8 @@ __device__ __forceinline__ void dma16_nt(const void *g, uint32_t lds_wave_base) 
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
-                                                             int tiles_m, int tiles_n, int slice_tiles, int xslices) {
+                                                             int tiles_m, int tiles_n, int slice_tiles, int xslices,
+                                                             const int *__restrict__ aux_tok, float aux_f) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int AB = WGM * TM, BB = WGN * TN;          // 32-row blocks per tile
     constexpr int RBU = KS * 64;                          // 16-byte units of one row block in one k-tile
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     constexpr bool PADDED = (UNITS % NT) != 0;           // s_waitcnt fits all; surplus copies go to a dump area
     static_assert((NS - 2) * NLOAD <= 63, "vmcnt is a 6-bit counter");
     static_assert(EPI != EPI_SILU_FRAG || TN % 2 == 0, "gate and up blocks must sit in the same wave");
+    constexpr bool TRANSPOSED = EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX || EPI == EPI_ROWSTATS;      // blocks with rows = weight rows
     constexpr int STAGE_BYTES = (AB + BB) * KS * 1024;
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
             for (int i = 0; i < TMV; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    if (EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX)   // transposed block: rows = weight rows, cols = activation rows
+                    if (TRANSPOSED)   // transposed block: rows = weight rows, cols = activation rows
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
                     else
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                 for (int i = 0; i < TMV; ++i)
 #pragma unroll
                     for (int j = 0; j < TNV; ++j) {
-                        if (EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX)
+                        if (TRANSPOSED)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
                         else
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
@@ -387,6 +389,41 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
             if (other > key) key = other;
             if (lh == 0 && row < M) atomicMax(keys + row, key);
         }
+    } else if (EPI == EPI_ROWSTATS) {
+        // Sampling passes need, per row, the softmax statistics at temperature 1/aux_f and the logit of the row's draft
+        // token -- not the logits.  Per 32-column block: a lane holds half of a row's block (16 columns, ascending, in its
+        // registers): m_h, then with the other half's lane m_b = max(m_0, m_1), z_h = sum of exp((l - m_b) * aux_f) in
+        // register order, z_b = z_0 + z_1 (the definition in k_head.hip, which the kernels there share).
+        // Cv: float2 [blocks][ldc] (m_b, z_b), followed by float [ldc] draft logits; aux_tok[row]: the draft token (or -1).
+        float2 *part = reinterpret_cast<float2 *>(Cv);
+        const int nblk = (N + 31) >> 5;
+        float *draft_logit = reinterpret_cast<float *>(part + (size_t)nblk * ldc);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + i * 32 + lr;
+            const int dt = row < M ? aux_tok[row] : -1;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c0 = n0 + j * 32;
+                if (j >= tnv || c0 >= N) continue;
+                float mh = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int col = c0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (col < N) mh = fmaxf(mh, acc[i][j][r]);
+                    if (col == dt) draft_logit[row] = acc[i][j][r];
+                }
+                const float mb = fmaxf(mh, __shfl_xor(mh, 32));
+                float zh = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int col = c0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (col < N) zh += __expf((acc[i][j][r] - mb) * aux_f);
+                }
+                const float zo = __shfl_xor(zh, 32);
+                if (lh == 0 && row < M) part[(size_t)(c0 >> 5) * ldc + row] = make_float2(mb, zh + zo);
+            }
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -409,7 +446,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
 
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                       int slice_tiles = 0, int slices = 1, bool slice_per_xcd = false) {
+                       int slice_tiles = 0, int slices = 1, bool slice_per_xcd = false, const int *aux_tok = nullptr, float aux_f = 0.f) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
@@ -422,11 +459,11 @@ static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, 
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     if (SL == 2 && slice_per_xcd && slices >= 2 && (8 % slices) == 0) {
         const int grid = ((tiles_m * tiles_n * slices + 7) / 8) * 8;
-        kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, slices);
+        kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, slices, aux_tok, aux_f);
         return;
     }
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    kern<<<dim3(grid, SL == 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, 0);
+    kern<<<dim3(grid, SL == 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, 0, aux_tok, aux_f);
 }
 
 // Sum of the slice partials in ascending order, then the epilogue.  ws: [slices][MN] fp32; MN % 4 == 0.
@@ -451,6 +488,9 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4 *__restri
         reinterpret_cast<uint2 *>(Cv)[i] = *reinterpret_cast<uint2 *>(o);
     }
 }
+
+// EPI_ROWSTATS is built for the many-row wide shape only: passes with fewer rows write their logits (they are small)
+bool gemm_rowstats_supported(int M, int N) { return M > 512 && N >= 16384; }
 
 // K slices of a narrow GEMM: a function of K alone (never of M), so that every launch shape sums in the same order
 int gemm_slices(int K, int *slice_tiles) {
@@ -500,9 +540,15 @@ static int cu_count() {
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats, const GemmNormTail *tail, int *left_slices) {
+                 float *ws, size_t ws_floats, const GemmNormTail *tail, int *left_slices, const int *aux_tok, float aux_f) {
     if (left_slices) *left_slices = 1;
     if (M <= 0) return false;
+    if (epi == EPI_ROWSTATS) {
+        // the LM head of a sampling pass with many rows (the caller checks gemm_rowstats_supported): the 256x256 tiles of
+        // the greedy head, with the statistics epilogue
+        launch_one<2, 2, 4, 4, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+        return false;
+    }
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
     //  * wide outputs (gate/up, LM head): 256x256 -- half the bytes per flop of a 128x128 tile through the HBM->LDS
     //    copy path, which is what saturates first -- on 4 waves of 128x128 with the pipelined k loop at many rows,

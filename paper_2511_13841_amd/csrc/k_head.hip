@@ -59,73 +59,94 @@ void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const
 }
 
 // ---------------------------------------------------------------- stochastic acceptance
-// row_stats[r] = (max logit, Z = sum exp((l - max)/T))
-__global__ __launch_bounds__(1024) void row_stats_kernel(const float *__restrict__ logits, int V, float inv_temp,
-                                                         float *__restrict__ stats) {
-    // one pass over the row: every thread keeps a running (max, sum of exp relative to that max) over its elements and
-    // the pairs are then combined in a fixed order (lanes by butterfly, waves in index order)
-    __shared__ float red_m[16], red_z[16];
-    const float *x = logits + (size_t)blockIdx.x * V;
-    float mx = -INFINITY, z = 0.f;
-    auto add = [&](float v) {
-        if (v > mx) { z = z * __expf((mx - v) * inv_temp) + 1.f; mx = v; }      // exp(-inf) = 0 on the first element
-        else z += __expf((v - mx) * inv_temp);
-    };
-    const int nv4 = V >> 2;
-    for (int c = threadIdx.x; c < nv4; c += 1024) {
-        const float4 v = reinterpret_cast<const float4 *>(x)[c];
-        add(v.x); add(v.y); add(v.z); add(v.w);
-    }
-    for (int i = (nv4 << 2) + threadIdx.x; i < V; i += 1024) add(x[i]);
-    auto merge = [&](float om, float oz) {
-        const float nm = fmaxf(mx, om);
-        if (nm == -INFINITY) return;                                          // both empty
-        z = z * __expf((mx - nm) * inv_temp) + oz * __expf((om - nm) * inv_temp);
-        mx = nm;
-    };
-    for (int o = 32; o > 0; o >>= 1) {
-        const float om = __shfl_xor(mx, o), oz = __shfl_xor(z, o);
-        merge(om, oz);
-    }
-    if ((threadIdx.x & 63) == 0) { red_m[threadIdx.x >> 6] = mx; red_z[threadIdx.x >> 6] = z; }
+// Everything here is DEFINED on per-block statistics of the logits, so that a pass that never writes its logits (the
+// LM-head GEMM emits the statistics from its accumulators) and a pass that does (inspection, small vocabularies) take
+// the same decisions bit for bit.  Block b = columns 32b .. 32b+31 of a row; the block is seen as two halves, half h
+// holding the columns c with (c >> 2) & 1 == h in ascending order (the registers of one lane of a 32x32 MFMA block):
+//     m_h = running maximum of half h,  m_b = max(m_0, m_1),
+//     z_h = sum over half h, in that order, of exp((l - m_b) / T),  z_b = z_0 + z_1.
+// Columns past the vocabulary take no part.  Row statistics (M, Z): eight chains, chain c merging the blocks
+// b = c, c+8, ... in ascending order, then the chains merged in ascending order, where merging (m, z) with (m', z')
+// gives (max, z e^{(m-max)/T} + z' e^{(m'-max)/T}).
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ void stats_merge(float &m, float &z, float om, float oz, float inv_temp) {
+    const float nm = fmaxf(m, om);
+    if (nm == -INFINITY) return;                                          // both empty
+    z = z * __expf((m - nm) * inv_temp) + oz * __expf((om - nm) * inv_temp);
+    m = nm;
+}
+
+// block statistics from written logits; grid (ceil(nblk / 256), rows), one thread per (row, block)
+__global__ __launch_bounds__(256) void block_stats_kernel(const float *__restrict__ logits, int V, int nblk, float inv_temp,
+                                                          const int *__restrict__ dtok, float2 *__restrict__ part, int ldp,
+                                                          float *__restrict__ draft_logit) {
+    const int row = blockIdx.y, b = blockIdx.x * 256 + threadIdx.x;
+    const float *x = logits + (size_t)row * V;
+    if (b == 0) { const int dt = dtok ? dtok[row] : -1; draft_logit[row] = dt >= 0 ? x[dt] : 0.f; }
+    if (b >= nblk) return;
+    float v[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) v[c] = 32 * b + c < V ? x[32 * b + c] : -INFINITY;
+    float mh[2] = {-INFINITY, -INFINITY};
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { const int c = 8 * (r >> 2) + 4 * h + (r & 3); if (32 * b + c < V) mh[h] = fmaxf(mh[h], v[c]); }
+    const float mb = fmaxf(mh[0], mh[1]);
+    float zh[2] = {0.f, 0.f};
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { const int c = 8 * (r >> 2) + 4 * h + (r & 3); if (32 * b + c < V) zh[h] += __expf((v[c] - mb) * inv_temp); }
+    part[(size_t)b * ldp + row] = make_float2(mb, zh[0] + zh[1]);
+}
+
+// row statistics from the block statistics; grid ceil(rows / 32), block 256 = 8 chains x 32 rows
+__global__ __launch_bounds__(256) void row_stats_merge_kernel(const float2 *__restrict__ part, int ldp, int nblk, int n_rows,
+                                                              float inv_temp, float2 *__restrict__ stats) {
+    __shared__ float2 chain[8][32];
+    const int rl = threadIdx.x & 31, c = threadIdx.x >> 5, row = blockIdx.x * 32 + rl;
+    float m = -INFINITY, z = 0.f;
+    if (row < n_rows)
+        for (int b = c; b < nblk; b += 8) { const float2 p = part[(size_t)b * ldp + row]; stats_merge(m, z, p.x, p.y, inv_temp); }
+    chain[c][rl] = make_float2(m, z);
     __syncthreads();
-    if (threadIdx.x == 0) {
-        mx = red_m[0]; z = red_z[0];
-        for (int w = 1; w < 16; ++w) merge(red_m[w], red_z[w]);
-        stats[2 * blockIdx.x] = mx;
-        stats[2 * blockIdx.x + 1] = z;
+    if (c == 0 && row < n_rows) {
+        for (int k = 1; k < 8; ++k) stats_merge(m, z, chain[k][rl].x, chain[k][rl].y, inv_temp);
+        stats[row] = make_float2(m, z);
     }
 }
 
-// One workgroup (16 waves) per sequence.  Rows j = 0..k-1: accept draft j+1 iff u_accept*Z < w(draft); the rows are tested
-// side by side, one per lane, and the first rejection is taken from a ballot.  Then an inverse-CDF draw (ascending
-// vocabulary order) from the row where the walk stopped, with the rejected draft's weight removed: wave w owns the
-// contiguous segment [w*seg, (w+1)*seg) and walks it in blocks of 256 consecutive columns (four per lane), recording the
-// total of every block; the 16 segment totals are added in order, and the wave whose segment holds the crossing finds
-// the block from its recorded totals and reads that block a second time to name the column.
-__device__ __forceinline__ float wave_inclusive_scan(float v, int lane) {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const float t = __shfl_up(v, o);
-        if (lane >= o) v += t;
-    }
-    return v;
-}
-#define SAMPLE_GROUPS 64
-__global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__restrict__ logits, int V,
-                                                             const int *__restrict__ tok, const int *__restrict__ b_row0,
-                                                             const int *__restrict__ b_n, float inv_temp,
-                                                             const float *__restrict__ u_accept,
-                                                             const float *__restrict__ u_sample, int prefill_mode,
-                                                             const float *__restrict__ stats, int *__restrict__ accept_len,
-                                                             int *__restrict__ next_token) {
-    __shared__ float seg_total[16];
-    __shared__ int seg_lastnz[16];
-    __shared__ int walk[2];          // accepted drafts, rejected token
-    __shared__ float grp_total[16][SAMPLE_GROUPS];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r0 = prefill_mode ? b : b_row0[b];
-    const int k = prefill_mode ? 0 : b_n[b] - 1;
+// One workgroup (256 threads) per sequence.
+//  1. Rows j = 0..k-1 (one per lane of wave 0): accept draft j+1 iff u_accept * Z < w(draft), w = exp((l_draft - M) / T);
+//     the first rejection is taken from a ballot: a = accepted drafts, `rejected` = the token that failed (-1: none).
+//  2. The token after row a is the inverse-CDF draw (ascending vocabulary order) from the row's weights with the rejected
+//     token's weight removed.  First the BLOCK that holds the crossing, from the block weights
+//         W_b = z_b e^{(m_b - M)/T}   (minus w(rejected), floored at zero, for the block that holds the rejected token):
+//     thread t adds its ceil(nblk/256) consecutive blocks in ascending order, the 256 sums are added in ascending order
+//     (total), target = u_sample * total, and the crossing is the first block at which the running sum exceeds the target.
+//  3. Then the column inside that block: wave 0 computes the block's 32 logits of that row again with the MFMA sequence of
+//     the LM-head GEMM (one pass over K, 16 at a time, from zero: the same bits) and walks them in ascending order from
+//     the running sum in front of the block.  If rounding keeps the walk below the target, the block's last column of
+//     non-zero weight is taken; the rejected token is never returned.
+// xsel: the normalised rows that got logits (fragment order, K = d); wlm: the LM head (fragment order).
+__global__ __launch_bounds__(256) void accept_sample_kernel(const float2 *__restrict__ part, int ldp, int nblk, int V,
+                                                            const float2 *__restrict__ stats, const float *__restrict__ draft_logit,
+                                                            const bf16_t *__restrict__ xsel, const bf16_t *__restrict__ wlm, int K,
+                                                            const int *__restrict__ tok, const int *__restrict__ b_row0,
+                                                            const int *__restrict__ b_n, float inv_temp,
+                                                            const float *__restrict__ u_accept, const float *__restrict__ u_sample,
+                                                            int prefill_mode, int *__restrict__ accept_len, int *__restrict__ next_token) {
+    __shared__ int walk[2];            // accepted drafts, rejected token
+    __shared__ float tsum[256];
+    __shared__ float found[4];         // crossing block, running sum in front of it, target, (flag)
+    __shared__ int last_nz_blk[256];
+    const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r0 = prefill_mode ? s : b_row0[s];
+    const int k = prefill_mode ? 0 : b_n[s] - 1;
     if (wave == 0) {
         int a = k, rejected = -1;
         for (int base = 0; base < k && a == k; base += 64) {
@@ -135,13 +156,13 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__rest
             if (jrow < k) {
                 const int r = r0 + jrow;
                 d = tok[r + 1];
-                const float mx = stats[2 * r], Z = stats[2 * r + 1];
-                const float wd = __expf((logits[(size_t)r * V + d] - mx) * inv_temp);
-                rej = !(u_accept[r] * Z < wd);
+                const float2 st = stats[r];
+                const float wd = __expf((draft_logit[r] - st.x) * inv_temp);
+                rej = !(u_accept[r] * st.y < wd);
             }
-            const unsigned long long m = __ballot(rej);
-            if (m) {
-                const int first = __ffsll((long long)m) - 1;
+            const unsigned long long mk = __ballot(rej);
+            if (mk) {
+                const int first = __ffsll((long long)mk) - 1;
                 a = base + first;
                 rejected = __shfl(d, first);
             }
@@ -151,135 +172,136 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *__rest
     __syncthreads();
     const int a = walk[0], rejected = walk[1];
     const int r = r0 + a;
-    const float *x = logits + (size_t)r * V;
-    const float mx = stats[2 * r];
-    const float u = prefill_mode ? u_sample[b] : u_sample[r];
-    // Columns per wave: a multiple of 256.  A wave walks its segment in blocks of 256 columns, four columns per lane (one
-    // 16-byte load when V is a multiple of 4), four blocks in flight.  The weights of a block are added as: each lane its four
-    // columns in order, then an inclusive scan over the lanes, so a running sum in index order exists at every column.
-    const int seg = (((V + 15) / 16) + 255) & ~255;
-    const int lo = wave * seg, hi = min(lo + seg, V);
-    const int nblk = hi > lo ? (hi - lo + 255) >> 8 : 0;          // blocks of this wave that hold columns
-    const int grp = ((seg >> 8) + SAMPLE_GROUPS - 1) / SAMPLE_GROUPS;      // blocks per recorded total (1 up to V = 262144)
-    const bool vec = (V & 3) == 0;
-    auto weights4 = [&](int i, float w[4]) {
-        float l[4];
-        if (vec && i + 3 < hi) {
-            const float4 v = *reinterpret_cast<const float4 *>(x + i);
-            l[0] = v.x; l[1] = v.y; l[2] = v.z; l[3] = v.w;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) l[e] = i + e < hi ? x[i + e] : -INFINITY;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (i + e < hi && i + e != rejected) ? __expf((l[e] - mx) * inv_temp) : 0.f;
+    const float M = stats[r].x;
+    const float u = prefill_mode ? u_sample[s] : u_sample[r];
+    const float wrej = rejected >= 0 ? __expf((draft_logit[r] - M) * inv_temp) : 0.f;
+    const int rej_blk = rejected >= 0 ? rejected >> 5 : -1;
+    auto block_weight = [&](int b) -> float {
+        const float2 p = part[(size_t)b * ldp + r];
+        float w = p.x == -INFINITY ? 0.f : p.y * __expf((p.x - M) * inv_temp);
+        if (b == rej_blk) w = fmaxf(w - wrej, 0.f);
+        return w;
     };
-    float run = 0.f, gsum = 0.f;
-    int nz = -1;
-    for (int b0 = 0; b0 < nblk; b0 += 4) {
-        float w[4][4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (b0 + q < nblk) weights4(lo + ((b0 + q) << 8) + 4 * lane, w[q]);
-            else w[q][0] = w[q][1] = w[q][2] = w[q][3] = 0.f;
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int blk = b0 + q;
-            if (blk >= nblk) break;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (w[q][e] > 0.f) nz = lo + (blk << 8) + 4 * lane + e;
-            const float ls = ((w[q][0] + w[q][1]) + w[q][2]) + w[q][3];
-            gsum += __shfl(wave_inclusive_scan(ls, lane), 63);
-            if (blk % grp == grp - 1 || blk == nblk - 1) {
-                if (lane == 0) grp_total[wave][blk / grp] = gsum;
-                run += gsum;
-                gsum = 0.f;
-            }
-        }
-    }
-    for (int o = 32; o > 0; o >>= 1) nz = max(nz, __shfl_xor(nz, o));
-    if (lane == 0) { seg_total[wave] = run; seg_lastnz[wave] = nz; }
-    __syncthreads();
-    float before = 0.f, total = 0.f;
-    int owner = -1;
+    const int per = (nblk + 255) / 256;
+    const int b_lo = min(tid * per, nblk), b_hi = min(b_lo + per, nblk);
     {
-        float c = 0.f;
-        for (int w = 0; w < 16; ++w) {
-            if (w == wave) before = c;
-            c += seg_total[w];
-        }
-        total = c;
+        float acc = 0.f;
+        int nz = -1;
+        for (int b = b_lo; b < b_hi; ++b) { const float w = block_weight(b); acc += w; if (w > 0.f) nz = b; }
+        tsum[tid] = acc;
+        last_nz_blk[tid] = nz;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float total = 0.f;
+        for (int t = 0; t < 256; ++t) total += tsum[t];
         const float target = u * total;
-        c = 0.f;
-        for (int w = 0; w < 16; ++w) {
-            c += seg_total[w];
-            if (owner < 0 && c > target) owner = w;
-        }
+        float c = 0.f;
+        int owner = -1;
+        for (int t = 0; t < 256 && owner < 0; ++t) { if (c + tsum[t] > target) owner = t; else c += tsum[t]; }
+        found[2] = target;
+        found[3] = (float)owner;
+        found[1] = c;                  // running sum in front of the owner's first block
     }
-    const float target = u * total;
-    if (wave == (owner < 0 ? 0 : owner)) {
-        int pick = -1;
-        if (owner >= 0) {
-            // the recorded totals name the group of blocks that holds the crossing; only that group is read again
-            float c = before;
-            const int ngrp = (nblk + grp - 1) / grp;
-            int g = 0;
-            for (; g < ngrp; ++g) {
-                const float t = grp_total[wave][g];
-                if (c + t > target) break;
-                c += t;
+    __syncthreads();
+    const float target = found[2];
+    const int owner = (int)found[3];
+    if (owner >= 0) {
+        if (tid == owner) {
+            float c = found[1];
+            int bsel = -1;
+            for (int b = b_lo; b < b_hi; ++b) {
+                const float w = block_weight(b);
+                if (c + w > target) { bsel = b; break; }
+                c += w;
             }
-            for (int blk = g * grp; g < ngrp && blk < min((g + 1) * grp, nblk) && pick < 0; ++blk) {
-                float w[4];
-                const int i = lo + (blk << 8) + 4 * lane;
-                weights4(i, w);
-                const float p0 = w[0], p1 = p0 + w[1], p2 = p1 + w[2], ls = p2 + w[3];
-                const float sc = wave_inclusive_scan(ls, lane);
-                float ex = __shfl_up(sc, 1);
-                if (lane == 0) ex = 0.f;
-                // this lane's candidate: its first column whose running sum passes the target, else its last non-zero one
-                const float pre[4] = {p0, p1, p2, ls};
-                int cand = -1;
+            if (bsel < 0) {            // the thread's total crossed but its walk did not (cannot differ: same additions); keep its last non-zero block
+                bsel = last_nz_blk[tid];
+                c = found[1];
+                for (int b = b_lo; b < bsel; ++b) c += block_weight(b);
+            }
+            found[0] = (float)bsel;
+            found[1] = c;
+        }
+    } else if (tid == 0) {             // rounding pushed the target past the total: the last block of non-zero weight
+        int tl = -1, bsel = -1;
+        for (int t = 0; t < 256; ++t) if (last_nz_blk[t] >= 0) tl = t;
+        float c = 0.f;
+        if (tl >= 0) {
+            bsel = last_nz_blk[tl];
+            for (int t = 0; t < tl; ++t) c += tsum[t];
+            for (int b = min(tl * per, nblk); b < bsel; ++b) c += block_weight(b);
+        }
+        found[0] = (float)bsel;
+        found[1] = c;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const int bsel = (int)found[0];
+    float c = found[1];
+    // the 32 logits of row r in block bsel: transposed 32x32 block (rows = weight rows = columns of the logits)
+    const int KF = K >> 4;
+    const uint4 *wp = reinterpret_cast<const uint4 *>(wlm) + (size_t)max(bsel, 0) * KF * 64 + lane;
+    const uint4 *ap = reinterpret_cast<const uint4 *>(xsel) + (size_t)(r >> 5) * KF * 64 + lane;
+    f32x16_t acc;
 #pragma unroll
-                for (int e = 3; e >= 0; --e)
-                    if (w[e] > 0.f && (cand < 0 || c + (ex + pre[e]) > target)) cand = e;
-                const unsigned long long m = __ballot(c + sc > target);
-                if (m) {
-                    const int L = __ffsll((long long)m) - 1;
-                    // (a lane of zero weights cannot be the first to pass, except by rounding in the scan: then the
-                    // nearest lane below it that holds a weight)
-                    const unsigned long long have = __ballot(cand >= 0) & ((2ull << L) - 1ull);
-                    if (have) pick = __shfl(i + cand, 63 - __clzll((long long)have));
-                }
-                c += __shfl(sc, 63);
+    for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+    for (int ks0 = 0; ks0 < KF; ks0 += 16) {      // sixteen k-steps' loads in flight together (past the end: the last one again, unused)
+        uint4 wv[16], av[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) { const size_t o = (size_t)min(ks0 + q, KF - 1) * 64; wv[q] = wp[o]; av[q] = ap[o]; }
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            if (ks0 + q < KF)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t *>(&wv[q]), *reinterpret_cast<const bf16x8_t *>(&av[q]), acc, 0, 0, 0);
+    }
+    // lane (lr, lh) holds, of activation row lr, the block's columns 8q + 4lh + e in register 4q + e: bring row r % 32 to every lane
+    float l[32];
+    const int src0 = r & 31, src1 = 32 + (r & 31);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            l[8 * q + e] = __shfl(acc[4 * q + e], src0);
+            l[8 * q + 4 + e] = __shfl(acc[4 * q + e], src1);
+        }
+    if (lane == 0) {
+        int pick = -1, last_nz = -1, first_ok = -1;
+        if (bsel >= 0) {
+#pragma unroll
+            for (int cc = 0; cc < 32; ++cc) {
+                const int col = 32 * bsel + cc;
+                if (col >= V || col == rejected) continue;
+                if (first_ok < 0) first_ok = col;
+                const float w = __expf((l[cc] - M) * inv_temp);
+                if (w > 0.f) last_nz = col;
+                c += w;
+                if (pick < 0 && c > target) pick = col;
             }
-            // the running sum starts at the segments before this one here and at zero in the first walk: if that rounds
-            // the last step below the target, the crossing is the segment's last non-zero weight
-            if (pick < 0) pick = seg_lastnz[wave];
+            if (pick < 0) pick = last_nz >= 0 ? last_nz : first_ok;
         }
-        if (pick < 0) {                                  // rounding pushed the target past the total: last non-zero weight
-            for (int w = 0; w < 16; ++w) pick = max(pick, seg_lastnz[w]);
-        }
-        if (lane == 0) {
-            accept_len[b] = a;
-            next_token[b] = pick;
-        }
+        if (pick < 0) pick = rejected == 0 ? 1 : 0;      // (a row without any weight: cannot happen for finite logits)
+        accept_len[s] = a;
+        next_token[s] = pick;
     }
 }
 
-void launch_sample(const float *logits, int V, const int *tok, const int *b_row0, const int *b_n, int NB,
-                   float inv_temp, const float *u_accept, const float *u_sample, int prefill_mode,
-                   float *row_stats, int *accept_len, int *next_token, hipStream_t st) {
-    // the caller passes the number of logit rows through b_n/b_row0 (verify) or NB (prefill: one row per sequence)
-    (void)row_stats;
-    accept_sample_kernel<<<dim3(NB), dim3(1024), 0, st>>>(logits, V, tok, b_row0, b_n, inv_temp, u_accept, u_sample,
-                                                        prefill_mode, row_stats, accept_len, next_token);
+void launch_block_stats(const float *logits, int n_rows, int V, float inv_temp, const int *dtok, float2 *part, int ldp,
+                        float *draft_logit, hipStream_t st) {
+    if (n_rows <= 0) return;
+    const int nblk = (V + 31) / 32;
+    block_stats_kernel<<<dim3((nblk + 255) / 256, n_rows), dim3(256), 0, st>>>(logits, V, nblk, inv_temp, dtok, part, ldp, draft_logit);
 }
-
-void launch_row_stats(const float *logits, int n_rows, int V, float inv_temp, float *stats, hipStream_t st) {
-    if (n_rows > 0) row_stats_kernel<<<dim3(n_rows), dim3(1024), 0, st>>>(logits, V, inv_temp, stats);
+void launch_row_stats_merge(const float2 *part, int ldp, int V, int n_rows, float inv_temp, float2 *stats, hipStream_t st) {
+    if (n_rows <= 0) return;
+    row_stats_merge_kernel<<<dim3((n_rows + 31) / 32), dim3(256), 0, st>>>(part, ldp, (V + 31) / 32, n_rows, inv_temp, stats);
+}
+void launch_sample(const float2 *part, int ldp, int V, const float2 *stats, const float *draft_logit, const bf16_t *xsel,
+                   const bf16_t *wlm, int K, const int *tok, const int *b_row0, const int *b_n, int NB, float inv_temp,
+                   const float *u_accept, const float *u_sample, int prefill_mode, int *accept_len, int *next_token, hipStream_t st) {
+    if (NB <= 0) return;
+    accept_sample_kernel<<<dim3(NB), dim3(256), 0, st>>>(part, ldp, (V + 31) / 32, V, stats, draft_logit, xsel, wlm, K, tok, b_row0, b_n,
+                                                       inv_temp, u_accept, u_sample, prefill_mode, accept_len, next_token);
 }
 
 // ---------------------------------------------------------------- row maxima gathered by the LM-head GEMM itself

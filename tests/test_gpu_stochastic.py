@@ -173,3 +173,63 @@ def test_inverse_cdf_walk_against_fp64_prefix_sums_of_the_gpu_logits(V):
                 assert int(nx[i]) != d1
             _check_sampled_token(w, float(us[row]), int(nx[i]), 1e-4)
     dm.free()
+
+
+def test_sampling_pass_without_logits_equals_the_pass_that_writes_them():
+    """A sampling pass of many rows never writes its logits: the LM-head GEMM leaves per-block softmax statistics and
+    the draft tokens' logits, and the drawing kernel computes the one block it needs again.  The same step in inspection
+    mode (logits written, statistics taken from them) must take the same decisions bit for bit; and those decisions are
+    right by fp64 arithmetic on the written logits (accept tests outside a 1e-5 band, tokens inside a 1e-4 window)."""
+    import paper_2511_13841_amd as das
+    V = 20011                                                       # not a multiple of 32: a ragged last block
+    shape = di.ModelShape("v20k", 1, 256, 4, 2, 64, 512, V, rope_theta=1.0e4)
+    blob = di.weights_bf16(shape, seed=5, sigma=0.25)
+    B, k, tau = 80, 7, 0.7
+    dm = das.DasModel(das.config_for(shape, max_seqs=B, max_ctx=128, max_rows=B * (k + 1), max_draft=k, num_pages=B * 4), blob)
+    rng = np.random.default_rng(3)
+    lens = rng.integers(5, 40, size=B)
+    ids = list(range(B))
+    dm.prefill(ids, di.prompts(lens, V, 9))
+    # likely drafts: the greedy chain of a plain pass for the first draft, random after it
+    acc, g1 = dm.verify_step(ids, lens, [[] for _ in ids])
+    dm.kv_rollback(ids)
+    drafts = [np.concatenate([[g1[i]], rng.integers(0, V, size=k - 1)]).astype(np.int32) for i in ids]
+    T = B * (k + 1)
+    for rnd in range(3):
+        ua = rng.random(T).astype(np.float32)
+        ua = np.where(rng.random(T) < 0.5, 0.0, ua).astype(np.float32)          # half of the tests forced to accept
+        us = rng.random(T).astype(np.float32)
+        us[:8] = [0.0, 1.0 - 2.0 ** -24, 0.5, 0.25, 0.75, 0.999, 0.001, 0.9]
+        acc1, nx1 = dm.verify_step(ids, lens, drafts, sampling=(tau, ua, us))
+        with pytest.raises(das.DasError):
+            dm.debug_logits(0, 1)                                    # nothing was written
+        dm.kv_rollback(ids)
+        dm.keep_logits(True)
+        acc2, nx2 = dm.verify_step(ids, lens, drafts, sampling=(tau, ua, us))
+        glog = dm.debug_logits()
+        dm.kv_rollback(ids)
+        dm.keep_logits(False)
+        assert np.array_equal(acc1, acc2) and np.array_equal(nx1, nx2)
+        n_rej = 0
+        for i in ids:
+            r0 = i * (k + 1)
+            a = 0
+            for j in range(k):
+                l = glog[r0 + j].astype(np.float64) / tau
+                p = np.exp(l - l.max()); p /= p.sum()
+                pd = p[drafts[i][j]]
+                if abs(ua[r0 + j] - pd) < 1e-5 * max(pd, 1e-30) + 1e-12:
+                    a = int(acc1[i]); break                          # on the edge: either decision is right
+                if not ua[r0 + j] < pd:
+                    break
+                a += 1
+            assert int(acc1[i]) == a, (rnd, i, int(acc1[i]), a)
+            l = glog[r0 + a].astype(np.float64) / tau
+            w = np.exp(l - l.max())
+            if a < k:
+                w[drafts[i][a]] = 0.0
+                assert int(nx1[i]) != int(drafts[i][a])
+                n_rej += 1
+            _check_sampled_token(w, float(us[r0 + a]), int(nx1[i]), 1e-4)
+        assert n_rej > 10
+    dm.free()
