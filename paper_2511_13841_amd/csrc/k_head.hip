@@ -65,8 +65,8 @@ void launch_accept_greedy(const int *g, const int *b_row0, const int *b_n, const
 // holding the columns c with (c >> 2) & 1 == h in ascending order (the registers of one lane of a 32x32 MFMA block):
 //     m_h = running maximum of half h,  m_b = max(m_0, m_1),
 //     z_h = sum over half h, in that order, of exp((l - m_b) / T),  z_b = z_0 + z_1.
-// Columns past the vocabulary take no part.  Row statistics (M, Z): eight chains, chain c merging the blocks
-// b = c, c+8, ... in ascending order, then the chains merged in ascending order, where merging (m, z) with (m', z')
+// Columns past the vocabulary take no part.  Row statistics (M, Z): 32 chains, chain c merging the blocks
+// b = c, c+32, ... in ascending order, then the chains merged in ascending order, where merging (m, z) with (m', z')
 // gives (max, z e^{(m-max)/T} + z' e^{(m'-max)/T}).
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -104,18 +104,26 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const float *__restric
     part[(size_t)b * ldp + row] = make_float2(mb, zh[0] + zh[1]);
 }
 
-// row statistics from the block statistics; grid ceil(rows / 32), block 256 = 8 chains x 32 rows
+// row statistics from the block statistics; grid ceil(rows / 8), block 256 = 32 chains x 8 rows (8 rows = one 64-byte
+// run of the [block][row] layout).  A chain's loads are independent of its arithmetic: eight are requested at a time.
 __global__ __launch_bounds__(256) void row_stats_merge_kernel(const float2 *__restrict__ part, int ldp, int nblk, int n_rows,
                                                               float inv_temp, float2 *__restrict__ stats) {
-    __shared__ float2 chain[8][32];
-    const int rl = threadIdx.x & 31, c = threadIdx.x >> 5, row = blockIdx.x * 32 + rl;
+    __shared__ float2 chain[32][8];
+    const int rl = threadIdx.x & 7, c = threadIdx.x >> 3, row = blockIdx.x * 8 + rl;
     float m = -INFINITY, z = 0.f;
-    if (row < n_rows)
-        for (int b = c; b < nblk; b += 8) { const float2 p = part[(size_t)b * ldp + row]; stats_merge(m, z, p.x, p.y, inv_temp); }
+    if (row < n_rows) {
+        for (int b0 = c; b0 < nblk; b0 += 32 * 8) {
+            float2 p[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { const int b = b0 + 32 * q; p[q] = b < nblk ? part[(size_t)b * ldp + row] : make_float2(-INFINITY, 0.f); }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) stats_merge(m, z, p[q].x, p[q].y, inv_temp);
+        }
+    }
     chain[c][rl] = make_float2(m, z);
     __syncthreads();
     if (c == 0 && row < n_rows) {
-        for (int k = 1; k < 8; ++k) stats_merge(m, z, chain[k][rl].x, chain[k][rl].y, inv_temp);
+        for (int k = 1; k < 32; ++k) stats_merge(m, z, chain[k][rl].x, chain[k][rl].y, inv_temp);
         stats[row] = make_float2(m, z);
     }
 }
@@ -187,7 +195,13 @@ __global__ __launch_bounds__(256) void accept_sample_kernel(const float2 *__rest
     {
         float acc = 0.f;
         int nz = -1;
-        for (int b = b_lo; b < b_hi; ++b) { const float w = block_weight(b); acc += w; if (w > 0.f) nz = b; }
+        for (int b0 = b_lo; b0 < b_hi; b0 += 8) {      // (the loads of eight blocks in flight together; added in ascending order)
+            float w[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) w[q] = b0 + q < b_hi ? block_weight(b0 + q) : 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) if (b0 + q < b_hi) { acc += w[q]; if (w[q] > 0.f) nz = b0 + q; }
+        }
         tsum[tid] = acc;
         last_nz_blk[tid] = nz;
     }
@@ -294,7 +308,7 @@ void launch_block_stats(const float *logits, int n_rows, int V, float inv_temp, 
 }
 void launch_row_stats_merge(const float2 *part, int ldp, int V, int n_rows, float inv_temp, float2 *stats, hipStream_t st) {
     if (n_rows <= 0) return;
-    row_stats_merge_kernel<<<dim3((n_rows + 31) / 32), dim3(256), 0, st>>>(part, ldp, (V + 31) / 32, n_rows, inv_temp, stats);
+    row_stats_merge_kernel<<<dim3((n_rows + 7) / 8), dim3(256), 0, st>>>(part, ldp, (V + 31) / 32, n_rows, inv_temp, stats);
 }
 void launch_sample(const float2 *part, int ldp, int V, const float2 *stats, const float *draft_logit, const bf16_t *xsel,
                    const bf16_t *wlm, int K, const int *tok, const int *b_row0, const int *b_n, int NB, float inv_temp,
