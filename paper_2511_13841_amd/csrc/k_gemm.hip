@@ -151,7 +151,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int rb0 = colsplit ? 0 : wm * TM;              // first row block and column block of this wave inside the tile
     const int cb0 = colsplit ? wave * 2 : wn * TN;
     const int tnv = colsplit ? 2 : TN;                   // column blocks this wave owns
+#ifdef DAS_GEMM_DEV
+    const int vb = aux_f == -12345.f ? 0 : min(TM, max(0, (M - (tile_m * AB + rb0) * 32 + 31) >> 5));      // copies only
+#else
     const int vb = min(TM, max(0, (M - (tile_m * AB + rb0) * 32 + 31) >> 5));
+#endif
     auto compute = [&](auto tm_tag, const unsigned char *cur, int next_kt, int next_stage) {
         constexpr int TMV = decltype(tm_tag)::value;      // row blocks 0 .. TMV-1 are multiplied
         // fragments of k-step ks+1 are requested before the MFMAs of k-step ks are issued
@@ -457,6 +461,9 @@ static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, 
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         configured = true;
     }
+#ifdef DAS_GEMM_DEV
+    { static int nm = -1; if (nm < 0) { const char *e = getenv("DAS_GEMM_NOMFMA"); nm = e ? atoi(e) : 0; } if (nm) aux_f = -12345.f; }
+#endif
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     if (SL == 2 && slice_per_xcd && slices >= 2 && (8 % slices) == 0) {
         const int grid = ((tiles_m * tiles_n * slices + 7) / 8) * 8;
@@ -523,6 +530,9 @@ static void launch_cfg3(int epi, const bf16_t *A, const bf16_t *W, void *C, int 
     }
 }
 
+#ifdef DAS_GEMM_DEV
+static int dev_variant() { static int v = -1; if (v < 0) { const char *e = getenv("DAS_GEMM_VARIANT"); v = e ? atoi(e) : 0; } return v; }
+#endif
 // Compute units of the current device (asked once; 256 if the query fails).
 static int cu_count() {
     static int n_cu = 0;
@@ -604,7 +614,18 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             // registers of the wave): 8 fragment reads per 16 MFMAs, a third less LDS traffic per MFMA than 8 waves of
             // 128x64.  k-tiles of 32 in a four-stage ring, k loop pipelined across k-tiles, requests dealt out one per
             // MFMA (see k_loop_pipe).  283 -> 251 us per layer at T = 1088 against the 8-wave loop the compiler scheduled.
-            launch_one<2, 2, 4, 4, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        {
+            // M tiles of EQUAL height: the fewest tiles of up to 256 rows, then the smallest height (in 32-row blocks) that
+            // covers M with that many.  A short last tile (T = 1088 = 4 x 256 + 64) ends early, the workgroups that follow it
+            // start out of phase with the others that share their weight tile, and the weight tile is streamed into L2 again
+            // for them: with five tiles of 224 rows (4 waves side by side, each 224x64) gate/up at 1088 rows fetches 500 MB
+            // instead of 760 MB and takes 240 instead of 250 us, although a 1 x 4 wave layout reads 9 fragments per 14 MFMAs.
+            const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
+            if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 5) launch_one<1, 4, 5, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else launch_one<2, 2, 4, 4, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        }
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
         return false;
     }
