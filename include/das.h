@@ -194,9 +194,12 @@ int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a, int32_t F,
  * Operands are random bf16 (N(0,1) activations, N(0,0.02^2) weights) generated on the device; `weight_sets`
  * distinct weight matrices are used in turn so that a launch does not find its weights in a cache left by the
  * previous one (a decoder touches each layer's weights once per pass).  *us_per_launch = mean over `iters`
- * launches after two warm-up launches.  Needs no model. */
+ * launches after two warm-up launches.  copies_only != 0 times the same launches with their arithmetic switched
+ * off: every workgroup moves the same tiles into LDS behind the same barriers and multiplies nothing (results are
+ * meaningless), which shows how much of a shape's time is its copy stream.  Needs no model; not for use while
+ * another thread launches verification passes (the switch is process-wide for the duration of the call). */
 int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t iters, int32_t weight_sets,
-                        double *us_per_launch);
+                        int32_t copies_only, double *us_per_launch);
 
 /* Device-to-device copy of `bytes` (multiple of 16) by a trivial kernel, `repeats` times: a dispatch of
  * known HBM traffic (bytes read + bytes written) against which profiler byte counters are scaled. */

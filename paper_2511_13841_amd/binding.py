@@ -65,7 +65,7 @@ def lib():
             "das_debug_seq": [P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I), VP, C.POINTER(I)],
             "das_debug_free_pages": [P, C.POINTER(C.c_int64)],
             "das_debug_kv_saturated": [P, C.POINTER(C.c_int64)],
-            "das_debug_gemm_time": [I, I, I, I, I, I, C.POINTER(C.c_double)],
+            "das_debug_gemm_time": [I, I, I, I, I, I, I, C.POINTER(C.c_double)],
             "das_debug_gemm": [I, I, I, VP, VP, VP],
             "das_debug_gemm_epilogues": [I, I, VP, I, VP, VP, VP, I, VP, VP],
             "das_gemm_noalloc": [I, I, I, VP, VP, VP, VP],
@@ -155,10 +155,12 @@ def debug_gemm_rowmax(a_bf16, w_bf16):
     return col
 
 
-def debug_gemm_time(epi, M, N, K, iters=20, weight_sets=4):
-    """Mean device time (us) of one projection GEMM launch of this shape; epi: 1 residual, 2 gate/up, 3 fp32 out, 4 row max."""
+def debug_gemm_time(epi, M, N, K, iters=20, weight_sets=4, copies_only=False):
+    """Mean device time (us) of one projection GEMM launch of this shape; epi: 1 residual, 2 gate/up, 3 fp32 out, 4 row max.
+    copies_only: the same launches with the arithmetic switched off (tile copies and barriers only)."""
     us = C.c_double()
-    _chk(lib().das_debug_gemm_time(int(epi), int(M), int(N), int(K), int(iters), int(weight_sets), C.byref(us)), "das_debug_gemm_time")
+    _chk(lib().das_debug_gemm_time(int(epi), int(M), int(N), int(K), int(iters), int(weight_sets), int(bool(copies_only)), C.byref(us)),
+         "das_debug_gemm_time")
     return us.value
 
 

@@ -13,7 +13,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
 
 def _compile(src):
     obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    dev = ["-DDAS_ATTN_DEV", "-DDAS_GEMM_DEV"] if os.environ.get("DAS_DEV_BUILD") else []     # kernel-part timing variants (see k_attn.hip)
+    dev = ["-DDAS_ATTN_DEV"] if os.environ.get("DAS_DEV_BUILD") else []     # kernel-part timing variants (see k_attn.hip)
     cmd = ["hipcc"] + FLAGS + dev + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)

@@ -1087,7 +1087,8 @@ extern "C" int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a,
 }
 
 // Device time of one projection GEMM shape with the launch configuration a pass would use (see das.h).
-extern "C" int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t iters, int32_t weight_sets, double *us_per_launch) {
+extern "C" int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t iters, int32_t weight_sets, int32_t copies_only,
+                                   double *us_per_launch) {
     if (M < 1 || N < 32 || K < 64 || (K % 64) || iters < 1 || weight_sets < 1 || weight_sets > 64 || !us_per_launch ||
         (epi != EPI_RESID_F32 && epi != EPI_SILU_FRAG && epi != EPI_F32_ROWMAJOR && epi != EPI_ROWMAX) ||
         (epi == EPI_SILU_FRAG && (N % 128)) || (epi == EPI_ROWMAX && N < 16384) || (epi != EPI_SILU_FRAG && epi != EPI_ROWMAX && (N % 4)))
@@ -1123,10 +1124,12 @@ extern "C" int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K,
             else if (epi == EPI_RESID_F32) launch_gemm(EPI_RESID_F32, a, wi, c, M, N, K, N, nullptr, ws, ws_floats, (N % 64) == 0 && N <= 8192 ? &tail : nullptr);
             else { int left = 1; launch_gemm(EPI_F32_ROWMAJOR, a, wi, c, M, N, K, N, nullptr, ws, ws_floats, nullptr, &left); }
         };
+        gemm_debug_copies_only(copies_only != 0);
         once(0); once(1);
-        if (bad(hipDeviceSynchronize())) break;
-        if (bad(hipEventRecord(e0, nullptr))) break;
+        if (bad(hipDeviceSynchronize())) { gemm_debug_copies_only(false); break; }
+        if (bad(hipEventRecord(e0, nullptr))) { gemm_debug_copies_only(false); break; }
         for (int it = 0; it < iters; ++it) once(it + 2);
+        gemm_debug_copies_only(false);
         if (bad(hipEventRecord(e1, nullptr)) || bad(hipEventSynchronize(e1))) break;
         float ms = 0.f;
         if (bad(hipEventElapsedTime(&ms, e0, e1))) break;

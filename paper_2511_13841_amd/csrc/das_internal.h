@@ -118,6 +118,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
                  float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr,
                  const int *aux_tok = nullptr, float aux_f = 0.f);
 bool gemm_rowstats_supported(int M, int N);
+void gemm_debug_copies_only(bool on);      // timing mode of das_debug_gemm_time: launches copy their tiles and multiply nothing
 int gemm_slices(int K, int *slice_tiles);
 // split-KV partial attention for the items of one row-block class, then the merge.  Sequences of one chunk are finished
 // by launch_attn itself (their rows go straight to out_frag, bit-equal to what the merge would write), so pm.mblk lists
