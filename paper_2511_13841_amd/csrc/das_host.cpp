@@ -455,9 +455,11 @@ static int load_impl(das_model *m, const uint16_t *wb, uint64_t seed) {
     A(m->cs, Mp * dm.D); A(m->logits, (size_t)c.max_rows * V); A(m->row_stats, (size_t)c.max_rows * 2);
     A(m->d_g, (size_t)c.max_rows); A(m->d_accept, (size_t)c.max_seqs); A(m->d_next, (size_t)c.max_seqs); A(m->d_keys, (size_t)c.max_rows);
     A(m->stat_part, (size_t)((V + 31) / 32) * c.max_rows + ((size_t)c.max_rows + 1) / 2);
-    {   // slice partials of the narrow GEMMs when a pass has at most 512 rows: [slices <= 8][rows][widest narrow output]
-        const size_t n_narrow = std::max<size_t>(std::max<size_t>(dm.qkvN, d), V < 16384 ? V : 0);
-        m->gemm_ws_floats = 8 * std::min<size_t>(512, Mp) * n_narrow;
+    {   // K-slice partials of the narrow GEMMs (QKV, O, down; a small LM head): whatever the largest pass can use
+        const int rows = c.max_rows;
+        size_t need = std::max(gemm_ws_floats_needed(rows, dm.qkvN, d), std::max(gemm_ws_floats_needed(rows, d, dm.Hq * dm.D), gemm_ws_floats_needed(rows, d, Fp)));
+        if (V < 16384) need = std::max(need, gemm_ws_floats_needed(rows, V, d));
+        m->gemm_ws_floats = std::max<size_t>(need, 4);
         A(m->gemm_ws, m->gemm_ws_floats);
     }
     HIPCHK(hipMemsetAsync(m->xn, 0, Mp * d * 2, m->st));
@@ -967,8 +969,7 @@ extern "C" int das_debug_gemm(int32_t M, int32_t N, int32_t K, const uint16_t *a
         if (bad(hipMalloc((void **)&da, (size_t)M * K * 2)) || bad(hipMalloc((void **)&dw, (size_t)N * K * 2)) ||
             bad(hipMalloc((void **)&pa, (size_t)Mp * Kp * 2)) || bad(hipMalloc((void **)&pw, (size_t)Np * Kp * 2)) ||
             bad(hipMalloc((void **)&dc, (size_t)M * N * 4))) break;
-        int slice_tiles = 0;
-        const size_t ws_floats = M <= 512 ? (size_t)gemm_slices(Kp, &slice_tiles) * M * N : 0;
+        const size_t ws_floats = gemm_ws_floats_needed(M, N, Kp);
         if (ws_floats && bad(hipMalloc((void **)&dws, ws_floats * 4))) break;
         if (bad(hipMemcpy(da, a, (size_t)M * K * 2, hipMemcpyHostToDevice)) || bad(hipMemcpy(dw, w, (size_t)N * K * 2, hipMemcpyHostToDevice))) break;
         launch_pack_weight(da, pa, M, K, Mp, Kp, nullptr);
@@ -1102,8 +1103,7 @@ extern "C" int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K,
     int rc = DAS_OK;
     auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
     do {
-        int slice_tiles = 0;
-        const size_t ws_floats = (size_t)gemm_slices(K, &slice_tiles) * std::min<size_t>(M, 512) * N;
+        const size_t ws_floats = std::max<size_t>(gemm_ws_floats_needed(M, N, K), 4);
         const size_t c_elems = epi == EPI_SILU_FRAG ? Mp * Fp / 2 + 1 : epi == EPI_ROWMAX ? 1 : (size_t)M * N;
         if (bad(hipMalloc((void **)&a, Mp * K * 2)) || bad(hipMalloc((void **)&w, Np * K * 2 * weight_sets)) ||
             bad(hipMalloc((void **)&c, c_elems * 4)) || bad(hipMalloc((void **)&ws, ws_floats * 4)) ||

@@ -93,7 +93,7 @@ void launch_pt_update(int *page_table, const int *upd, int n_upd, hipStream_t st
 void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStream_t st);
 // y (fragment order, K = d) = rmsnorm(h[row]) for row = sel ? sel[i] : i, i < n
 void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, int n, int d, float eps, hipStream_t st);
-void launch_reduce_resid_rmsnorm(const float *ws, int slices, float *h, const bf16_t *g, bf16_t *y, int n, int d, float eps, hipStream_t st);
+void launch_reduce_resid_rmsnorm(const float *ws, int slices, int group, float *h, const bf16_t *g, bf16_t *y, int n, int d, float eps, hipStream_t st);
 // RMSNorm that follows a residual GEMM (EPI_RESID_F32): when the GEMM's K slices are summed by a second kernel anyway, that
 // kernel also normalises the finished rows (gain g, output y in fragment order) and launch_gemm returns true; otherwise the
 // caller runs launch_rmsnorm itself.  Same bits either way.
@@ -120,6 +120,8 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
 bool gemm_rowstats_supported(int M, int N);
 void gemm_debug_copies_only(bool on);      // timing mode of das_debug_gemm_time: launches copy their tiles and multiply nothing
 int gemm_slices(int K, int *slice_tiles);
+int gemm_slice_group(int slices);                       // eight slices are added as two groups of four (0: one ascending run)
+size_t gemm_ws_floats_needed(int M, int N, int K);     // workspace that lets launch_gemm pick its fastest shape
 // split-KV partial attention for the items of one row-block class, then the merge.  Sequences of one chunk are finished
 // by launch_attn itself (their rows go straight to out_frag, bit-equal to what the merge would write), so pm.mblk lists
 // only the row blocks of sequences with two or more chunks.

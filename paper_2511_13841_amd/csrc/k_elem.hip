@@ -105,7 +105,7 @@ void launch_embed(const PassMeta &pm, const bf16_t *E, float *h, int d, hipStrea
 template <int MAXC, int WPR, bool FUSED = false>      // 8-element groups per lane the registers can hold (d <= MAXC * 512); waves per row
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const bf16_t *__restrict__ g,
                                                       bf16_t *__restrict__ y, const int *__restrict__ sel, int n, int d, float eps,
-                                                      const float4 *__restrict__ ws = nullptr, int slices = 0, size_t slab4 = 0) {
+                                                      const float4 *__restrict__ ws = nullptr, int slices = 0, size_t slab4 = 0, int group = 0) {
     static_assert(MAXC % 4 == 0 && (WPR == 1 || WPR == 4), "four partial sums per lane");
     __shared__ float part[WPR == 4 ? 4 * 64 : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -125,11 +125,22 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
             a[t] = reinterpret_cast<const float4 *>(x)[2 * c]; b[t] = reinterpret_cast<const float4 *>(x)[2 * c + 1];
             if (FUSED) {
                 const float4 *p = ws + (size_t)i * (d / 4) + 2 * c;
+                const int n1 = group > 0 ? group : slices;      // (group > 0: two runs, [0, group) and [group, slices), then their sum)
                 float4 ta = p[0], tb = p[1];
-                for (int s2 = 1; s2 < slices; ++s2) {
+                for (int s2 = 1; s2 < n1; ++s2) {
                     const float4 va = p[(size_t)s2 * slab4], vb = p[(size_t)s2 * slab4 + 1];
                     ta.x += va.x; ta.y += va.y; ta.z += va.z; ta.w += va.w;
                     tb.x += vb.x; tb.y += vb.y; tb.z += vb.z; tb.w += vb.w;
+                }
+                if (n1 < slices) {
+                    float4 ua = p[(size_t)n1 * slab4], ub = p[(size_t)n1 * slab4 + 1];
+                    for (int s2 = n1 + 1; s2 < slices; ++s2) {
+                        const float4 va = p[(size_t)s2 * slab4], vb = p[(size_t)s2 * slab4 + 1];
+                        ua.x += va.x; ua.y += va.y; ua.z += va.z; ua.w += va.w;
+                        ub.x += vb.x; ub.y += vb.y; ub.z += vb.z; ub.w += vb.w;
+                    }
+                    ta.x += ua.x; ta.y += ua.y; ta.z += ua.z; ta.w += ua.w;
+                    tb.x += ub.x; tb.y += ub.y; tb.z += ub.z; tb.w += ub.w;
                 }
                 a[t].x += ta.x; a[t].y += ta.y; a[t].z += ta.z; a[t].w += ta.w;
                 b[t].x += tb.x; b[t].y += tb.y; b[t].z += tb.z; b[t].w += tb.w;
@@ -177,15 +188,15 @@ void launch_rmsnorm(const float *h, const bf16_t *g, bf16_t *y, const int *sel, 
     if (n >= 1024) launch_rmsnorm_shape<1>(hh, g, y, sel, n, d, eps, st);
     else launch_rmsnorm_shape<4>(hh, g, y, sel, n, d, eps, st);
 }
-// h[i] += sum of the slice partials ws[s][i] (ascending s), then y = rmsnorm(h[i]) in fragment order; n < 1024 rows
-void launch_reduce_resid_rmsnorm(const float *ws, int slices, float *h, const bf16_t *g, bf16_t *y, int n, int d, float eps, hipStream_t st) {
+// h[i] += sum of the slice partials ws[s][i] (ascending s; in two runs when group > 0), then y = rmsnorm(h[i]) in fragment order
+void launch_reduce_resid_rmsnorm(const float *ws, int slices, int group, float *h, const bf16_t *g, bf16_t *y, int n, int d, float eps, hipStream_t st) {
     if (n <= 0) return;
     const dim3 grid(n), block(256);
     const float4 *w4 = reinterpret_cast<const float4 *>(ws);
     const size_t slab4 = (size_t)n * d / 4;
-    if (d <= 2048) rmsnorm_kernel<4, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4);
-    else if (d <= 4096) rmsnorm_kernel<8, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4);
-    else rmsnorm_kernel<16, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4);
+    if (d <= 2048) rmsnorm_kernel<4, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4, group);
+    else if (d <= 4096) rmsnorm_kernel<8, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4, group);
+    else rmsnorm_kernel<16, 4, true><<<grid, block, 0, st>>>(h, g, y, nullptr, n, d, eps, w4, slices, slab4, group);
 }
 
 // ---------------------------------------------------------------- RoPE angles, once per pass

@@ -40,7 +40,12 @@ __device__ __forceinline__ void dma16_nt(const void *g, uint32_t lds_wave_base) 
 // of `slice_tiles` k-tiles, each slice accumulated from zero and the slices added in ascending order, so that few-row
 // launches can spread the slices over workgroups without changing a single bit of the result:
 // 1: this workgroup walks all slices and folds each finished slice into a second set of registers;
-// 2: this workgroup computes slice blockIdx.y and stores the raw fp32 partial to slab blockIdx.y of Cv ([slices][M][ldc]).
+// 2: this workgroup computes slice blockIdx.y and stores the raw fp32 partial to slab blockIdx.y of Cv ([slices][M][ldc]);
+// 3: this workgroup walks the `xslices` slices of group blockIdx.y, folds them like 1 and stores the group's sum to slab
+//    blockIdx.y of Cv ([groups][M][ldc]).
+// A sum of eight slices (K >= 16384) is DEFINED as two groups of four, (((s0+s1)+s2)+s3) + (((s4+s5)+s6)+s7), so that the
+// two halves of a long K can go to two workgroups (mode 3) and meet in one addition; with mode 1 `xslices` = 4 asks for
+// that grouping inside one workgroup (only the small-tile kernels have the registers for it).
 // PIPE: the k loop is pipelined across k-tiles and its instruction order is pinned (see k_loop_pipe).
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
@@ -74,7 +79,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     } else {
         const int per_xcd = (nt + 7) >> 3;
         t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-        if (SL == 2) slice = blockIdx.y;
+        if (SL >= 2) slice = blockIdx.y;
     }
     if (t >= nt) return;
     const int tile_m = t % tiles_m, tile_n = t / tiles_m;
@@ -83,9 +88,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int wm = wave / WGN, wn = wave % WGN;
     const int KF = K >> 4;                                 // fragments per row block
     const int KT = K / (16 * KS);                          // k-tiles
-    const int kt_begin = SL == 2 ? slice * slice_tiles : 0;
-    const int kt_end = SL == 2 ? min(KT, kt_begin + slice_tiles) : KT;
-    if (SL == 2) Cv = reinterpret_cast<float *>(Cv) + (size_t)slice * M * ldc;
+    const int wg_tiles = SL == 3 ? xslices * slice_tiles : slice_tiles;      // k-tiles of this workgroup (modes 2, 3)
+    const int kt_begin = SL >= 2 ? slice * wg_tiles : 0;
+    const int kt_end = SL >= 2 ? min(KT, kt_begin + wg_tiles) : KT;
+    if (SL >= 2) Cv = reinterpret_cast<float *>(Cv) + (size_t)slice * M * ldc;
     const uint4 *Ag = reinterpret_cast<const uint4 *>(A);
     const uint4 *Wg = reinterpret_cast<const uint4 *>(W);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem + wave * 1024;
@@ -96,7 +102,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     for (int j = 0; j < NLOAD; ++j) {
         const int u = min(tid + j * NT, UNITS - 64 + lane);      // surplus waves re-read the last fragment
         if (u < A_UNITS) src[j] = Ag + ((size_t)(tile_m * AB + u / RBU) * KF) * 64 + (u % RBU);
-        else { const int v = u - A_UNITS; src[j] = Wg + ((size_t)(tile_n * BB + v / RBU) * KF) * 64 + (v % RBU); }
+        else {      // (tiles whose width does not divide 256 reach past the padded weight rows: those copies re-read the last block)
+            const int v = u - A_UNITS, wb = min(tile_n * BB + v / RBU, ((N + 255) >> 8) * 8 - 1);
+            src[j] = Wg + ((size_t)wb * KF) * 64 + (v % RBU);
+        }
     }
     // surplus copies of the last pass (whole waves: UNITS is a multiple of 64) land behind the ring
     const bool surplus = PADDED && (wave * 64 + (NLOAD - 1) * NT >= UNITS);
@@ -189,25 +198,46 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     const int last = kt_end - 1;
 #pragma unroll
     for (int s0 = 0; s0 < NS - 1; ++s0) issue(min(kt_begin + s0, last), s0);
-    f32x16 tot[SL == 1 ? TM : 1][SL == 1 ? TN : 1];      // SL == 1: sum of the finished slices
-    if (SL == 1) {
+    constexpr bool FOLD = SL == 1 || SL == 3;            // slices folded in registers
+    constexpr bool GROUPS = SL == 1 && TM * TN <= 2;     // ... and two groups of slices kept apart (see above)
+    f32x16 tot[FOLD ? TM : 1][FOLD ? TN : 1];            // sum of the finished slices
+    f32x16 first[GROUPS ? TM : 1][GROUPS ? TN : 1];      // sum of the first group
+    int folds = 0;
+    if (FOLD) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) tot[SL == 1 ? i : 0][SL == 1 ? j : 0][r] = 0.f;
+                for (int r = 0; r < 16; ++r) tot[FOLD ? i : 0][FOLD ? j : 0][r] = 0.f;
     }
-    auto fold = [&]() {
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto fold = [&]() {      // (whole-vector operations: element loops over nine blocks are not unrolled and would put acc in memory)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j) {
+                tot[FOLD ? i : 0][FOLD ? j : 0] += acc[i][j];
+                acc[i][j] = zero16;
+            }
+        if (GROUPS && xslices > 0 && ++folds == xslices) {      // the first group is complete: the second starts from zero
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    tot[SL == 1 ? i : 0][SL == 1 ? j : 0][r] += acc[i][j][r];
-                    acc[i][j][r] = 0.f;
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    first[GROUPS ? i : 0][GROUPS ? j : 0] = tot[FOLD ? i : 0][FOLD ? j : 0];
+                    tot[FOLD ? i : 0][FOLD ? j : 0] = zero16;
                 }
+        }
+    };
+    auto total = [&]() {      // after the last fold: the sum of all slices goes back to acc for the epilogue
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                acc[i][j] = tot[FOLD ? i : 0][FOLD ? j : 0];
+                if (GROUPS && xslices > 0 && folds >= xslices) acc[i][j] = first[GROUPS ? i : 0][GROUPS ? j : 0] + acc[i][j];
+            }
     };
     // one copy of the whole k loop per variant (the choice is made once per wave, outside the loop)
     auto k_loop = [&](auto tm_tag) {
@@ -220,14 +250,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
             if (decltype(tm_tag)::value == 0) issue(min(kt + NS - 1, last), refill);
             else compute(tm_tag, smem + stage * STAGE_BYTES, min(kt + NS - 1, last), refill);
             stage = stage == NS - 1 ? 0 : stage + 1;
-            if (SL == 1 && decltype(tm_tag)::value != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
+            if (FOLD && decltype(tm_tag)::value != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
         }
-        if (SL == 1 && decltype(tm_tag)::value != 0) {      // the last, possibly shorter slice; then the total goes to the epilogue
-            fold();
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = tot[SL == 1 ? i : 0][SL == 1 ? j : 0];
+        if (FOLD && decltype(tm_tag)::value != 0) {      // the last, possibly shorter slice; then the total goes to the epilogue
+            if (in_slice) fold();
+            total();
         }
     };
     // PIPE: the k loop pipelined across k-tiles.  The barrier that publishes tile kt+1 sits before the LAST k-step of tile
@@ -312,16 +339,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                     }
             }
             stage = next_stage;
-            if (SL == 1 && TMV != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
+            if (FOLD && TMV != 0 && ++in_slice == slice_tiles) { fold(); in_slice = 0; }
         };
         for (int kt = kt_begin; kt < kt_end - 1; ++kt) tile(kt, std::false_type{});
         tile(kt_end - 1, std::true_type{});
-        if (SL == 1 && TMV != 0) {
-            fold();
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = tot[SL == 1 ? i : 0][SL == 1 ? j : 0];
+        if (FOLD && TMV != 0) {
+            if (in_slice) fold();
+            total();
         }
     };
     if (PIPE) {
@@ -453,7 +477,8 @@ void gemm_debug_copies_only(bool on) { g_copies_only = on; }
 
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                       int slice_tiles = 0, int slices = 1, bool slice_per_xcd = false, const int *aux_tok = nullptr, float aux_f = 0.f) {
+                       int slice_tiles = 0, int slices = 1, bool slice_per_xcd = false, const int *aux_tok = nullptr, float aux_f = 0.f,
+                       int group = 0) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
@@ -470,18 +495,29 @@ static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, 
         return;
     }
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    kern<<<dim3(grid, SL == 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, 0, aux_tok, aux_f, (int)g_copies_only);
+    // mode 2: one workgroup per slice; mode 3: `slices` groups of `group` slices; mode 1: `group` = slices of the first group (0: one run)
+    kern<<<dim3(grid, SL >= 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, group, aux_tok, aux_f, (int)g_copies_only);
 }
 
-// Sum of the slice partials in ascending order, then the epilogue.  ws: [slices][MN] fp32; MN % 4 == 0.
+// Sum of the slice partials in ascending order (in two groups when group > 0: slices [0, group) and [group, slices), each
+// in ascending order, then the two sums added), then the epilogue.  ws: [slices][MN] fp32; MN % 4 == 0.
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4 *__restrict__ ws, int slices, size_t mn4, void *__restrict__ Cv) {
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4 *__restrict__ ws, int slices, int group, size_t mn4, void *__restrict__ Cv) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= mn4) return;
+    const int n1 = group > 0 ? group : slices;
     float4 t = ws[i];
-    for (int s2 = 1; s2 < slices; ++s2) {
+    for (int s2 = 1; s2 < n1; ++s2) {
         const float4 v = ws[(size_t)s2 * mn4 + i];
         t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+    }
+    if (n1 < slices) {
+        float4 u = ws[(size_t)n1 * mn4 + i];
+        for (int s2 = n1 + 1; s2 < slices; ++s2) {
+            const float4 v = ws[(size_t)s2 * mn4 + i];
+            u.x += v.x; u.y += v.y; u.z += v.z; u.w += v.w;
+        }
+        t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
     }
     if (EPI == EPI_RESID_F32) {
         float4 *c = reinterpret_cast<float4 *>(Cv) + i;
@@ -505,6 +541,17 @@ int gemm_slices(int K, int *slice_tiles) {
     const int want = KT >= 256 ? 8 : KT >= 48 ? 4 : KT >= 16 ? 2 : 1;
     *slice_tiles = (KT + want - 1) / want;
     return (KT + *slice_tiles - 1) / *slice_tiles;
+}
+// ... and how they are added: eight slices as two groups of four (0 = one ascending run)
+int gemm_slice_group(int slices) { return slices == 8 ? 4 : 0; }
+// Workspace (floats) that lets launch_gemm pick its fastest shape for a narrow output of M x N over K
+size_t gemm_ws_floats_needed(int M, int N, int K) {
+    int slice_tiles = 0;
+    const int slices = gemm_slices(K, &slice_tiles);
+    if (slices == 1) return 0;
+    const size_t few = (size_t)slices * (size_t)(M < 512 ? M : 512) * N;
+    const size_t many = (gemm_slice_group(slices) > 0 && M > 512) ? (size_t)2 * M * N : 0;
+    return few > many ? few : many;
 }
 
 template <int WGM, int WGN, int TM, int TN, int NS>
@@ -645,6 +692,29 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         return false;
     }
     const size_t mn = (size_t)M * N;
+    const int group = gemm_slice_group(slices);
+    const bool halves192 = ((M + 191) / 192) * ((N + 191) / 192) * 2 <= cu_count(), halves256 = ((M + 255) / 256) * ((N + 191) / 192) * 2 <= cu_count();
+    if (M > 512 && group > 0 && ws && ldc == N && (N % 4) == 0 && ws_floats >= 2 * mn && (halves192 || halves256)) {
+        // Many rows, long K (the down projection): 128x128 tiles over all of K move 32 KiB per k-tile of 64 and the launch
+        // runs at the speed of that copy stream.  When they fit the chip in one round, the two slice groups of the sum go to
+        // two workgroups instead, each with a tile of 192x192 over half of K: a quarter fewer bytes per multiply through
+        // L2 -> LDS for the same number of workgroups; 4 waves (2 x 2) of 3x3 blocks (accumulators and the folded slices
+        // fill the register file), pipelined k loop, k-tiles of 32; with more rows a tile of 256x192 on 8 waves (4 x 2) of
+        // 2x3 blocks.  The kernel that adds the two halves also adds the residual and applies the RMSNorm that follows.
+        if (halves192) launch_one<2, 2, 3, 3, 6, EPI_F32_ROWMAJOR, 2, true, 3, true>(A, W, ws, M, N, K, N, st, 2 * slice_tiles, 2, false, nullptr, 0.f, group);
+        else launch_one<4, 2, 2, 3, 5, EPI_F32_ROWMAJOR, 2, true, 3, true>(A, W, ws, M, N, K, N, st, 2 * slice_tiles, 2, false, nullptr, 0.f, group);
+        if (epi == EPI_RESID_F32 && tail) {
+            launch_reduce_resid_rmsnorm(ws, 2, 0, reinterpret_cast<float *>(C), tail->g, tail->y, M, N, tail->eps, st);
+            return true;
+        }
+        const size_t mn4 = mn / 4;
+        const dim3 g((unsigned)((mn4 + 255) / 256));
+        const float4 *w4 = reinterpret_cast<const float4 *>(ws);
+        if (epi == EPI_RESID_F32) gemm_reduce_kernel<EPI_RESID_F32><<<g, 256, 0, st>>>(w4, 2, 0, mn4, C);
+        else if (epi == EPI_BF16_ROWMAJOR) gemm_reduce_kernel<EPI_BF16_ROWMAJOR><<<g, 256, 0, st>>>(w4, 2, 0, mn4, C);
+        else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, 2, 0, mn4, C);
+        return false;
+    }
     // few rows: slices over workgroups when the tile grid alone would not fill the chip or K is long
     const bool few_tiles = M <= 64 || ((M + 127) / 128) * ((N + 63) / 64) < 200 || K >= 8192;
     if (M <= 512 && few_tiles && ws && ldc == N && (N % 4) == 0 && ws_floats >= mn * slices) {
@@ -669,20 +739,20 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         const dim3 g((unsigned)((mn4 + 255) / 256));
         const float4 *w4 = reinterpret_cast<const float4 *>(ws);
         if (epi == EPI_RESID_F32 && tail) {      // the kernel that adds the partials also normalises the finished rows
-            launch_reduce_resid_rmsnorm(ws, slices, reinterpret_cast<float *>(C), tail->g, tail->y, M, N, tail->eps, st);
+            launch_reduce_resid_rmsnorm(ws, slices, group, reinterpret_cast<float *>(C), tail->g, tail->y, M, N, tail->eps, st);
             return true;
         }
-        if (epi == EPI_F32_ROWMAJOR && left_slices) { *left_slices = slices; return false; }      // the caller's next kernel adds them
-        if (epi == EPI_RESID_F32) gemm_reduce_kernel<EPI_RESID_F32><<<g, 256, 0, st>>>(w4, slices, mn4, C);
-        else if (epi == EPI_BF16_ROWMAJOR) gemm_reduce_kernel<EPI_BF16_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
-        else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, mn4, C);
+        if (epi == EPI_F32_ROWMAJOR && left_slices && group == 0) { *left_slices = slices; return false; }      // the caller's next kernel adds them (one ascending run)
+        if (epi == EPI_RESID_F32) gemm_reduce_kernel<EPI_RESID_F32><<<g, 256, 0, st>>>(w4, slices, group, mn4, C);
+        else if (epi == EPI_BF16_ROWMAJOR) gemm_reduce_kernel<EPI_BF16_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, group, mn4, C);
+        else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, group, mn4, C);
         return false;
     }
     if (M <= 512) {      // few rows, enough tiles (QKV at a few hundred rows): 128x64 tiles, slices folded in registers
         switch (epi) {
-        case EPI_BF16_ROWMAJOR: launch_one<2, 2, 2, 1, 5, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
-        case EPI_RESID_F32: launch_one<2, 2, 2, 1, 5, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
-        default: launch_one<2, 2, 2, 1, 5, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        case EPI_BF16_ROWMAJOR: launch_one<2, 2, 2, 1, 5, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        case EPI_RESID_F32: launch_one<2, 2, 2, 1, 5, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        default: launch_one<2, 2, 2, 1, 5, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
         }
         return false;
     }
@@ -695,16 +765,16 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     const long cost192 = (long)((((M + 191) / 192) * tn + n_cu - 1) / n_cu) * 192;
     if (cost192 < cost128) {
         switch (epi) {
-        case EPI_BF16_ROWMAJOR: launch_one<3, 4, 2, 1, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
-        case EPI_RESID_F32: launch_one<3, 4, 2, 1, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
-        default: launch_one<3, 4, 2, 1, 3, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+        case EPI_BF16_ROWMAJOR: launch_one<3, 4, 2, 1, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        case EPI_RESID_F32: launch_one<3, 4, 2, 1, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        default: launch_one<3, 4, 2, 1, 3, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
         }
         return false;
     }
     switch (epi) {
-    case EPI_BF16_ROWMAJOR: launch_one<2, 4, 2, 1, 4, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
-    case EPI_RESID_F32: launch_one<2, 4, 2, 1, 4, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
-    default: launch_one<2, 4, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices); break;
+    case EPI_BF16_ROWMAJOR: launch_one<2, 4, 2, 1, 4, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+    case EPI_RESID_F32: launch_one<2, 4, 2, 1, 4, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+    default: launch_one<2, 4, 2, 1, 4, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
     }
     return false;
 }

@@ -16,7 +16,8 @@ def das():
 @pytest.mark.parametrize("M,N,K", [(20, 512, 256), (272, 384, 704), (130, 2048, 256), (1, 32, 64), (300, 1408, 256), (520, 16512, 192), (257, 16384, 64), (560, 16640, 192),
                                    (40, 320, 1024), (300, 256, 3584), (530, 192, 3136), (64, 128, 16448), (513, 96, 16384),
                                    (600, 16384, 64), (1030, 16448, 320), (320, 16400, 128), (450, 16384, 192),
-                                   (272, 2048, 16384), (160, 2176, 16448), (230, 2048, 16384)])
+                                   (272, 2048, 16384), (160, 2176, 16448), (230, 2048, 16384),
+                                   (700, 400, 16384), (1090, 200, 18944), (2250, 2048, 16384)])      # many rows, long K: the two halves of K in two workgroups; or grouped in one
 def test_mfma_gemm_against_fp64(das, M, N, K):
     rng = np.random.default_rng(M * 7 + N)
     a = di.f32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
@@ -73,17 +74,19 @@ def test_row_maximum_epilogue_against_fp64(das, M, N, K):
     assert np.all(ref[open_rows, got[open_rows]] >= ref[open_rows].max(axis=1) - 1e-4 * np.sqrt(K) * np.abs(ref).max())
 
 
-@pytest.mark.parametrize("N,K", [(320, 3584), (192, 18944), (16416, 1024), (256, 960), (2048, 16384)])
-def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K):
-    """A row of the product is the same bits whether it is computed among 7, 70, 300 or 600 rows: narrow outputs sum
-    K in slices whose layout depends on K alone, whichever kernel shape (slices over workgroups, or folded in
-    registers) the row count selects; wide outputs sum K in one pass at every row count."""
+@pytest.mark.parametrize("N,K,rows", [(320, 3584, 600), (192, 18944, 600), (16416, 1024, 600), (256, 960, 600), (2048, 16384, 600),
+                                      (400, 16384, 1100), (2048, 16384, 2250), (2048, 16384, 3000)])
+def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K, rows):
+    """A row of the product is the same bits whether it is computed among 7, 70, 300, 600 or 2250 rows: narrow outputs
+    sum K in slices whose layout and grouping depend on K alone, whichever kernel shape the row count selects (slices
+    over workgroups, folded in registers, the two slice groups of a long K in two workgroups on 192- or 256-row tiles,
+    or -- too many tiles for one round, 3000 rows -- grouped inside one workgroup); wide outputs sum K in one pass at every row count."""
     rng = np.random.default_rng(N + K)
-    a = di.f32_to_bf16(rng.standard_normal((600, K)).astype(np.float32))
+    a = di.f32_to_bf16(rng.standard_normal((rows, K)).astype(np.float32))
     w = di.f32_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
     full = das.debug_gemm(a, w)
     for m in (7, 70, 150, 300, 520):      # (N = 2048, K = 16384 at 150 and 300 rows: all rows in one workgroup per column tile)
-        print(f"gemm rows {m} of 600, N={N} K={K}", flush=True)
+        print(f"gemm rows {m} of {rows}, N={N} K={K}", flush=True)
         part = das.debug_gemm(a[:m], w)
         assert np.array_equal(part, full[:m]), (m, float(np.abs(part - full[:m]).max()))
 
