@@ -201,6 +201,19 @@ int das_debug_gemm_epilogues(int32_t M, int32_t K, const uint16_t *a, int32_t F,
 int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t iters, int32_t weight_sets,
                         int32_t copies_only, double *us_per_launch);
 
+/* The HBM/L2 -> LDS copy ring that feeds the GEMM and attention kernels, run by itself over synthetic buffers: a
+ * measurement of what the ring delivers, against which the kernels' copy streams are read.  `workgroups` workgroups of
+ * 4 waves (one per compute unit: the launch reserves more than half of a CU's LDS) each pull `tiles` tiles through a
+ * ring of `stages` stages; a tile is 4 * `copies` KiB, every wave issuing `copies` 1-KiB copies per tile, the first
+ * `shared_copies` of them from a 64-tile region that all workgroups read (L2 hits), the others from the workgroup's
+ * own stream (every line once: L2 misses; with the non-temporal hint if `non_temporal`).  Built (stages, copies,
+ * shared_copies): (4,4,0) (9,4,0) (4,9,0) (4,4,4) (9,4,4) (4,9,9) (4,9,6) (4,9,3) (5,7,5) (3,7,5), anything else is
+ * DAS_ERR_INVALID; tiles <= 4096, workgroups <= 1024.  *us = time of one launch (best of three after a
+ * warm-up; every launch reads private bytes no earlier launch touched), *bytes_into_lds = bytes one launch copies.
+ * Allocates and frees its buffers; needs no model. */
+int das_debug_copy_ring(int32_t workgroups, int32_t stages, int32_t copies, int32_t shared_copies, int32_t tiles,
+                        int32_t non_temporal, double *us, double *bytes_into_lds);
+
 /* Device-to-device copy of `bytes` (multiple of 16) by a trivial kernel, `repeats` times: a dispatch of
  * known HBM traffic (bytes read + bytes written) against which profiler byte counters are scaled. */
 int das_debug_copy(int64_t bytes, int32_t repeats);

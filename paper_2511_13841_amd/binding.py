@@ -70,6 +70,7 @@ def lib():
             "das_debug_gemm_epilogues": [I, I, VP, I, VP, VP, VP, I, VP, VP],
             "das_gemm_noalloc": [I, I, I, VP, VP, VP, VP],
             "das_debug_copy": [C.c_int64, I],
+            "das_debug_copy_ring": [I, I, I, I, I, I, C.POINTER(C.c_double), C.POINTER(C.c_double)],
             "das_profile_enable": [P, I],
             "das_profile_reset": [P],
             "das_profile_read": [P, I, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
@@ -162,6 +163,14 @@ def debug_gemm_time(epi, M, N, K, iters=20, weight_sets=4, copies_only=False):
     _chk(lib().das_debug_gemm_time(int(epi), int(M), int(N), int(K), int(iters), int(weight_sets), int(bool(copies_only)), C.byref(us)),
          "das_debug_gemm_time")
     return us.value
+
+
+def debug_copy_ring(workgroups, stages, copies, shared_copies, tiles=256, non_temporal=False):
+    """The kernels' HBM/L2 -> LDS copy ring by itself: (us per launch, bytes copied into LDS by one launch)."""
+    us, nb = C.c_double(), C.c_double()
+    _chk(lib().das_debug_copy_ring(int(workgroups), int(stages), int(copies), int(shared_copies), int(tiles), int(bool(non_temporal)),
+                                   C.byref(us), C.byref(nb)), "das_debug_copy_ring")
+    return us.value, nb.value
 
 
 def debug_copy(nbytes, repeats=1):

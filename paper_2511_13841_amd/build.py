@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 SO = os.path.join(HERE, "libdas.so")
-SOURCES = ["das_host.cpp", "das_budget.cpp", "das_drafter.cpp", "k_elem.hip", "k_gemm.hip", "k_attn.hip", "k_head.hip"]
+SOURCES = ["das_host.cpp", "das_budget.cpp", "das_drafter.cpp", "k_elem.hip", "k_gemm.hip", "k_attn.hip", "k_head.hip", "k_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result", "-Wno-inline-asm"]
 

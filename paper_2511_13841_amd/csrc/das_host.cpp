@@ -1157,6 +1157,42 @@ extern "C" int das_debug_copy(int64_t bytes, int32_t repeats) {
     return rc;
 }
 
+// The copy ring of the kernels with nothing else in it (see k_probe.hip): time of one launch, best of three after a warm-up
+// launch, each over a part of the private buffer that no earlier launch has touched.
+extern "C" int das_debug_copy_ring(int32_t workgroups, int32_t stages, int32_t copies, int32_t shared_copies, int32_t tiles,
+                                   int32_t non_temporal, double *us, double *bytes_into_lds) {
+    if (workgroups < 1 || workgroups > 1024 || tiles < 1 || tiles > 4096 || shared_copies < 0 || shared_copies > copies ||
+        !copy_ring_supported(stages, copies, shared_copies) || !us || !bytes_into_lds) return DAS_ERR_INVALID;
+    const int reps = 4;
+    const size_t per_launch = (size_t)workgroups * tiles * 4 * (copies - shared_copies) * 1024;      // private bytes of one launch
+    const size_t shared_bytes = (size_t)64 * 4 * std::max(shared_copies, 1) * 1024;
+    if (per_launch * reps > ((size_t)16 << 30)) return DAS_ERR_INVALID;
+    void *priv = nullptr, *sh = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = DAS_OK;
+    auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
+    do {
+        if (bad(hipMalloc(&priv, std::max<size_t>(per_launch * reps, 1024))) || bad(hipMalloc(&sh, shared_bytes)) ||
+            bad(hipMemset(priv, 1, std::max<size_t>(per_launch * reps, 1024))) || bad(hipMemset(sh, 1, shared_bytes)) ||
+            bad(hipEventCreate(&e0)) || bad(hipEventCreate(&e1)) || bad(hipDeviceSynchronize())) break;
+        float best = 0.f;
+        for (int r = 0; r < reps && rc == DAS_OK; ++r) {
+            const unsigned char *p = reinterpret_cast<const unsigned char *>(priv) + (size_t)r * per_launch;
+            if (bad(hipEventRecord(e0, nullptr)) || bad(launch_copy_ring(p, sh, workgroups, stages, copies, shared_copies, tiles, non_temporal != 0, nullptr)) ||
+                bad(hipEventRecord(e1, nullptr)) || bad(hipEventSynchronize(e1))) break;
+            float ms = 0.f;
+            if (bad(hipEventElapsedTime(&ms, e0, e1))) break;
+            if (r >= 1 && (best == 0.f || ms < best)) best = ms;
+        }
+        *us = (double)best * 1e3;
+        *bytes_into_lds = (double)workgroups * tiles * 4 * copies * 1024;
+    } while (0);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(priv); (void)hipFree(sh);
+    return rc;
+}
+
 // ------------------------------------------------------------------------------------------------ profiling / errors
 
 extern "C" int das_profile_enable(das_model *m, int32_t on) {

@@ -118,6 +118,10 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
                  float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr,
                  const int *aux_tok = nullptr, float aux_f = 0.f);
 bool gemm_rowstats_supported(int M, int N);
+// copy-ring probe (k_probe.hip): stages x (4 * copies) KiB ring, 4 waves; the built shapes are listed there
+bool copy_ring_supported(int stages, int copies, int shared_copies);
+hipError_t launch_copy_ring(const void *priv, const void *shared_r, int workgroups, int stages, int copies, int shared_copies,
+                            int tiles, bool non_temporal, hipStream_t st);
 void gemm_debug_copies_only(bool on);      // timing mode of das_debug_gemm_time: launches copy their tiles and multiply nothing
 int gemm_slices(int K, int *slice_tiles);
 int gemm_slice_group(int slices);                       // eight slices are added as two groups of four (0: one ascending run)

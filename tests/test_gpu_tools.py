@@ -33,3 +33,25 @@ def test_projection_timing_with_and_without_arithmetic():
         print(p)
         assert 1.0 < p["us"] < 5000.0 and 0.3 * p["us"] < p["us_copies_only"] < 1.15 * p["us"], p
         assert 0.0 < p["frac_of_floor"] <= 1.0, p
+
+
+def test_copy_ring_probe_shows_what_bounds_the_copy_streams():
+    """das_debug_copy_ring, the kernels' HBM/L2 -> LDS ring by itself.  What the kernel design rests on: (i) with few
+    busy CUs a stream of L2 misses does not speed up with a deeper ring (a cap on what one CU keeps in flight, not the
+    ring, bounds it); (ii) the non-temporal hint raises that stream's rate; (iii) copies that hit L2 arrive at more
+    than twice the rate of misses; (iv) with every CU busy a pure miss stream is bound by HBM, far below the sum of
+    the per-CU rates."""
+    import paper_2511_13841_amd as das
+    rate = lambda wgs, st, cp, sh, nt=False: (lambda us, nb: nb / us / 1e3 / wgs)(*das.debug_copy_ring(wgs, st, cp, sh, tiles=256, non_temporal=nt))
+    miss4, miss9 = rate(32, 4, 4, 0), rate(32, 9, 4, 0)
+    miss_nt, hit = rate(32, 4, 4, 0, True), rate(32, 4, 4, 4)
+    full = rate(256, 4, 4, 0, True)
+    print(f"GB/s per CU: misses {miss4:.1f} (4 stages) {miss9:.1f} (9 stages), non-temporal {miss_nt:.1f}, hits {hit:.1f}; all CUs non-temporal {full:.1f} = {full * 256 / 1e3:.2f} TB/s")
+    assert 20.0 < miss4 < 200.0
+    assert miss9 < 1.2 * miss4                   # (i)
+    assert miss_nt > 1.3 * miss4                 # (ii)
+    assert hit > 2.0 * miss4                     # (iii)
+    assert 4.0 < full * 256 / 1e3 < 8.0          # (iv) TB/s, under the 8 TB/s peak
+    assert full < 0.6 * miss_nt
+    with pytest.raises(das.DasError):
+        das.debug_copy_ring(32, 7, 4, 0)         # unsupported ring shape
