@@ -600,7 +600,12 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     if (epi == EPI_ROWSTATS) {
         // the LM head of a sampling pass with many rows (the caller checks gemm_rowstats_supported): the 256x256 tiles of
         // the greedy head, with the statistics epilogue
-        launch_one<2, 2, 4, 4, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+        // (M tiles of equal height, as for gate/up at many rows below)
+        const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
+        if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+        else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+        else if (hb == 5) launch_one<1, 4, 5, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+        else launch_one<2, 2, 4, 4, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
         return false;
     }
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
@@ -649,7 +654,13 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             else if (rows96) launch_one<1, 4, 3, 2, 7, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else launch_one<1, 4, 4, 2, 6, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         }
-        else if (epi == EPI_ROWMAX && M > 512) launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        else if (epi == EPI_ROWMAX && M > 512) {      // (M tiles of equal height, as for gate/up at many rows below)
+            const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
+            if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 5) launch_one<1, 4, 5, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        }
         else if (epi == EPI_F32_ROWMAJOR && M > 512) launch_one<2, 2, 4, 4, 4, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
         else if (epi == EPI_SILU_FRAG)
