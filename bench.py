@@ -210,7 +210,8 @@ def measure(args, name, K, W, with_cpu_baseline):
         "mean_accept_len": accepted / (K * ro.B),
         "whole_step": {"algorithmic_bytes": w_bytes + kv_bytes, "hbm_frac": (w_bytes + kv_bytes) / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9),
                        "floor_ms": floor_ms, "floor_over_time": floor_ms / ms},
-        "context_s": ro.context_s, "context_tokens_per_s": int(ro.ctx0.sum()) / ro.context_s if args.context == "prefill" else None,
+        "context_s": ro.context_s, "prefill_s": ro.context_s if args.context == "prefill" else None,
+        "context_tokens_per_s": int(ro.ctx0.sum()) / ro.context_s if args.context == "prefill" else None,
         "roofline": roof, "roofline_attention": roof_attn, "cpu_baseline": cpu,
         "ms_per_step_with_events": ms_prof, "kernels": kernels,
     }
