@@ -228,7 +228,8 @@ def main():
     ap.add_argument("--also", default=None,
                     help="comma-separated further workloads timed after the headline one and reported under `workloads` "
                          "(default: c4,c2,c5 when the headline is c3 with default settings; 'none' for none)")
-    ap.add_argument("--context", default="synth", choices=["synth", "prefill"])
+    ap.add_argument("--context", default="prefill", choices=["synth", "prefill"],
+                    help="how the contexts come to be: real das_prefill of random prompts (default), or synthetic KV written on the device")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--drafts", default="trajectory", choices=["trajectory", "random"],
@@ -248,7 +249,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs an MI355X; no HIP device is visible")
     K, W = args.steps, args.warmup
-    plain = args.batch is None and args.layers is None and args.context == "synth" and not args.rollback and \
+    plain = args.batch is None and args.layers is None and not args.rollback and \
         args.drafts == "trajectory" and not args.calibrate_copy and not args.faithful
     also = args.also if args.also is not None else ("c4,c2,c5" if args.workload == "c3" and plain else "none")
     also = [w for w in also.split(",") if w and w != "none" and w != args.workload]
@@ -272,6 +273,7 @@ def main():
         others[name] = {
             "ms_per_step": r["ms_per_step"], "emitted_tokens_per_s": r["value"], "accepted_draft_tokens_per_s": r["accepted_draft_tokens_per_s"],
             "steps": K, "warmup": W, "config": r["config"], "whole_step": r["whole_step"],
+            "prefill_s": r.get("prefill_s"), "context_tokens_per_s": r.get("context_tokens_per_s"),
             "attention": r["roofline_attention"] and {k: r["roofline_attention"][k] for k in ("achieved", "peak", "unit", "frac", "ms_per_launch", "share_of_step")},
             "dominant_gemm": dom and {"kernel": dom, **{k: gemms[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac", "ms_per_launch")}},
             "kernels_ms_per_step": {k: v["ms_per_step"] for k, v in kern.items()},
