@@ -46,7 +46,8 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_wave_base) {
 // makes the compiler keep the MFMA accumulators in ordinary VGPRs, where the (rare) rescale can reach them
 // without copies out of the accumulation register file on every tile.
 // DBG != 0 exists only in development builds (see launch_attn): 1 copies only, 6 arithmetic only (no copies after
-// the first two tiles), 7 copies only and no partial stores, 8 copies and LDS fragment reads without arithmetic.
+// the first two tiles), 7 copies only and no partial stores, 8 copies and LDS fragment reads without arithmetic, 9 everything
+// but with the partial results stored to a small region that stays in the caches.
 template <int D, int RBW, int NS, int MINW, int NW, int DBG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm, const int *__restrict__ items,
                                                            const f16_t *__restrict__ q_h,
@@ -291,7 +292,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void attn_partial_kernel(PassMeta pm
         l += __shfl_xor(l, 32);
         const int rb = wave * RBW + i;
         if (rb < nrb && DBG != 7) {
-            const size_t id = ((size_t)pm.b_prow[b] + (size_t)chunk * nrb + rb) * Hkv + kvh;
+            const size_t id = DBG == 9 ? ((size_t)blockIdx.x & 63) * 64 + rb * Hkv + kvh : ((size_t)pm.b_prow[b] + (size_t)chunk * nrb + rb) * Hkv + kvh;
             const float inv = l > 0.f ? 1.f / l : 0.f;
             if (single) {
                 const int rr = rb * 16 + (lane & 15);
@@ -367,6 +368,7 @@ void launch_attn(const PassMeta &pm, const int *items, int n_items, int rbw, con
         case 61: launch_attn_cfg<128, 1, 6>(ATTN_ARGS); return; case 62: launch_attn_cfg<128, 2, 6>(ATTN_ARGS); return;
         case 71: launch_attn_cfg<128, 1, 7>(ATTN_ARGS); return; case 72: launch_attn_cfg<128, 2, 7>(ATTN_ARGS); return;
         case 81: launch_attn_cfg<128, 1, 8>(ATTN_ARGS); return; case 82: launch_attn_cfg<128, 2, 8>(ATTN_ARGS); return;
+        case 91: launch_attn_cfg<128, 1, 9>(ATTN_ARGS); return; case 92: launch_attn_cfg<128, 2, 9>(ATTN_ARGS); return;
         }
     }
 #endif
