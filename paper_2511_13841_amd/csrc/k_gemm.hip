@@ -604,7 +604,6 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
         if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
         else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
-        else if (hb == 5) launch_one<1, 4, 5, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
         else launch_one<2, 2, 4, 4, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
         return false;
     }
@@ -658,7 +657,6 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
             if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
-            else if (hb == 5) launch_one<1, 4, 5, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         }
         else if (epi == EPI_F32_ROWMAJOR && M > 512) launch_one<2, 2, 4, 4, 4, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
@@ -670,14 +668,13 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             // MFMA (see k_loop_pipe).  283 -> 251 us per layer at T = 1088 against the 8-wave loop the compiler scheduled.
         {
             // M tiles of EQUAL height: the fewest tiles of up to 256 rows, then the smallest height (in 32-row blocks) that
-            // covers M with that many.  A short last tile (T = 1088 = 4 x 256 + 64) ends early, the workgroups that follow it
+            // covers M with that many (6, 7 or 8 blocks: more than 16 blocks in tiles of at most 8 never give 5).  A short last tile (T = 1088 = 4 x 256 + 64) ends early, the workgroups that follow it
             // start out of phase with the others that share their weight tile, and the weight tile is streamed into L2 again
             // for them: with five tiles of 224 rows (4 waves side by side, each 224x64) gate/up at 1088 rows fetches 500 MB
             // instead of 760 MB and takes 240 instead of 250 us, although a 1 x 4 wave layout reads 9 fragments per 14 MFMAs.
             const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
             if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
-            else if (hb == 5) launch_one<1, 4, 5, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else launch_one<2, 2, 4, 4, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         }
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);

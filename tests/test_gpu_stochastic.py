@@ -175,7 +175,8 @@ def test_inverse_cdf_walk_against_fp64_prefix_sums_of_the_gpu_logits(V):
     dm.free()
 
 
-def test_sampling_pass_without_logits_equals_the_pass_that_writes_them():
+@pytest.mark.parametrize("B", [80, 70])      # 640 and 560 rows: LM-head tiles of 7 and of 6 row blocks
+def test_sampling_pass_without_logits_equals_the_pass_that_writes_them(B):
     """A sampling pass of many rows never writes its logits: the LM-head GEMM leaves per-block softmax statistics and
     the draft tokens' logits, and the drawing kernel computes the one block it needs again.  The same step in inspection
     mode (logits written, statistics taken from them) must take the same decisions bit for bit; and those decisions are
@@ -184,7 +185,7 @@ def test_sampling_pass_without_logits_equals_the_pass_that_writes_them():
     V = 20011                                                       # not a multiple of 32: a ragged last block
     shape = di.ModelShape("v20k", 1, 256, 4, 2, 64, 512, V, rope_theta=1.0e4)
     blob = di.weights_bf16(shape, seed=5, sigma=0.25)
-    B, k, tau = 80, 7, 0.7
+    k, tau = 7, 0.7
     dm = das.DasModel(das.config_for(shape, max_seqs=B, max_ctx=128, max_rows=B * (k + 1), max_draft=k, num_pages=B * 4), blob)
     rng = np.random.default_rng(3)
     lens = rng.integers(5, 40, size=B)
