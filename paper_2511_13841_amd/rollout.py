@@ -34,7 +34,8 @@ class Rollout:
         self.horizon = grow
         pages = int(sum(-(-(int(c) + grow) // 16) for c in self.ctx0)) + 64
         max_ctx = -(-(int(self.ctx0.max()) + grow + 16) // 16) * 16
-        max_rows = max(self.B * (self.kmax + 1), 256)
+        # (a prefill pass takes up to max_rows prompt tokens and streams the weights once: room for 2048 of them)
+        max_rows = max(self.B * (self.kmax + 1), 2048 if context == "prefill" else 256)
         # random-init weights N(0, 0.02^2) from seed 0, drawn on the device by the library (the same values as
         # das_inputs.weights_bf16(shape, 0), which is generated on the host only if somebody asks for `blob`)
         self._blob = None
