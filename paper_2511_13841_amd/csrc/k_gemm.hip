@@ -667,14 +667,29 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             // 128x64.  k-tiles of 32 in a four-stage ring, k loop pipelined across k-tiles, requests dealt out one per
             // MFMA (see k_loop_pipe).  283 -> 251 us per layer at T = 1088 against the 8-wave loop the compiler scheduled.
         {
-            // M tiles of EQUAL height: the fewest tiles of up to 256 rows, then the smallest height (in 32-row blocks) that
-            // covers M with that many (6, 7 or 8 blocks: more than 16 blocks in tiles of at most 8 never give 5).  A short last tile (T = 1088 = 4 x 256 + 64) ends early, the workgroups that follow it
+            // M tiles of EQUAL height (3 .. 8 blocks of 32 rows).  A short last tile (T = 1088 = 4 x 256 + 64) ends early, the workgroups that follow it
             // start out of phase with the others that share their weight tile, and the weight tile is streamed into L2 again
             // for them: with five tiles of 224 rows (4 waves side by side, each 224x64) gate/up at 1088 rows fetches 500 MB
             // instead of 760 MB and takes 240 instead of 250 us, although a 1 x 4 wave layout reads 9 fragments per 14 MFMAs.
-            const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
+            // Which equal height: the launch takes about (rounds of workgroups) x (time of one tile), a tile of h row blocks
+            // about (h + 4) units (measured at K = 3584: 49, 56, 62, 70, 82, 89 us for h = 3 .. 8), and a last round counts
+            // in full unless it is nearly empty (measured on 148 column tiles: 296 and 444 workgroups on 256 CUs take the
+            // same time).  E.g. 384 rows: three tiles of 128 (444 workgroups, 112 us) instead of two of 192 (296, 139 us);
+            // 448 rows: three of 160 (124 against 151 us); 896 rows: five of 192 (218 against 232 us).
+            const int mb = (M + 31) / 32, tn = (N + 255) / 256, cus = cu_count();
+            int hb = 8;
+            double best = 1e30;
+            for (int h = 8; h >= 3; --h) {
+                const double x = (double)((mb + h - 1) / h) * tn / cus, whole = (double)(long)x, frac = x - whole;
+                const double rounds = frac <= 0 ? whole : x <= 2.0 ? whole + 1 : whole + (frac > 0.4 ? 1.0 : 0.6 + frac);
+                const double cost = rounds * (h + 4);
+                if (cost < best * 0.999) { best = cost; hb = h; }
+            }
             if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 5) launch_one<1, 4, 5, 2, 5, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 4) launch_one<1, 4, 4, 2, 6, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 3) launch_one<1, 4, 3, 2, 7, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else launch_one<2, 2, 4, 4, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         }
         else launch_cfg<2, 4, 4, 2, 2>(epi, A, W, C, M, N, K, ldc, st);
