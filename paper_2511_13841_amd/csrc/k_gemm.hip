@@ -589,6 +589,23 @@ static int cu_count() {
 }
 
 
+// Height, in 32-row blocks, of the equal M tiles of a wide GEMM (256-column tiles) with M rows: lo .. 8.  The launch takes
+// about (rounds of workgroups) x (time of one tile); a tile of h row blocks takes about (h + 4) units (measured at
+// K = 3584: 49, 56, 62, 70, 82, 89 us for h = 3 .. 8), and a last round counts in full unless it is nearly empty (measured
+// on 148 column tiles: 296 and 444 workgroups on 256 CUs take the same time).  Ties go to the taller tile.
+static int pick_tile_height(int M, int N, int lo) {
+    const int mb = (M + 31) / 32, tn = (N + 255) / 256, cus = cu_count();
+    int hb = 8;
+    double best = 1e30;
+    for (int h = 8; h >= lo; --h) {
+        const double x = (double)((mb + h - 1) / h) * tn / cus, whole = (double)(long)x, frac = x - whole;
+        const double rounds = frac <= 0 ? whole : x <= 2.0 ? whole + 1 : whole + (frac > 0.4 ? 1.0 : 0.6 + frac);
+        const double cost = rounds * (h + 4);
+        if (cost < best * 0.999) { best = cost; hb = h; }
+    }
+    return hb;
+}
+
 // A must be allocated for M rounded up to 256 rows plus another 256 (tiles of 96, 192 or 288 rows read past a multiple
 // of 256), W for N rounded up to 256 rows; K % 64 == 0.
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
@@ -601,7 +618,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // the LM head of a sampling pass with many rows (the caller checks gemm_rowstats_supported): the 256x256 tiles of
         // the greedy head, with the statistics epilogue
         // (M tiles of equal height, as for gate/up at many rows below)
-        const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
+        const int hb = pick_tile_height(M, N, 6);
         if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
         else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
         else launch_one<2, 2, 4, 4, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
@@ -647,17 +664,19 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // ... and at 257..512 rows on 4 waves of 128x64 or 96x64 (128x256 or 96x256 tiles), whichever pads M less:
         // 221 -> 186 us for the 1.5B head at 320 rows against 256x256 tiles of 8 waves
         const bool rows96 = (M + 95) / 96 * 96 < (M + 127) / 128 * 128;
-        if (M <= 512 && pad288 >= pad256 && (epi == EPI_ROWMAX || epi == EPI_F32_ROWMAJOR)) {      // (up to 288 rows: one 288-row tile, below)
-            if (epi == EPI_ROWMAX && rows96) launch_one<1, 4, 3, 2, 7, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
-            else if (epi == EPI_ROWMAX) launch_one<1, 4, 4, 2, 6, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
-            else if (rows96) launch_one<1, 4, 3, 2, 7, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
-            else launch_one<1, 4, 4, 2, 6, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
-        }
-        else if (epi == EPI_ROWMAX && M > 512) {      // (M tiles of equal height, as for gate/up at many rows below)
-            const int mb = (M + 31) / 32, n_tiles = (mb + 7) / 8, hb = (mb + n_tiles - 1) / n_tiles;
+        if (epi == EPI_ROWMAX && (M > 512 || pad288 >= pad256)) {      // (up to 288 rows: one 288-row tile, below)
+            // M tiles of equal height, as for gate/up at many rows below: e.g. 448 rows are two tiles of 224, not five of 96
+            const int hb = pick_tile_height(M, N, 3);
             if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 5) launch_one<1, 4, 5, 2, 5, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 4) launch_one<1, 4, 4, 2, 6, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 3) launch_one<1, 4, 3, 2, 7, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+        }
+        else if (M <= 512 && pad288 >= pad256 && epi == EPI_F32_ROWMAJOR) {
+            if (rows96) launch_one<1, 4, 3, 2, 7, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else launch_one<1, 4, 4, 2, 6, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         }
         else if (epi == EPI_F32_ROWMAJOR && M > 512) launch_one<2, 2, 4, 4, 4, EPI_F32_ROWMAJOR, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
         else if (pad288 < pad256 && epi != EPI_SILU_FRAG) launch_cfg3<3, 4, 3, 2, 2>(epi, A, W, C, M, N, K, ldc, st);   // (slower with the SiLU epilogue)
@@ -671,20 +690,10 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
             // start out of phase with the others that share their weight tile, and the weight tile is streamed into L2 again
             // for them: with five tiles of 224 rows (4 waves side by side, each 224x64) gate/up at 1088 rows fetches 500 MB
             // instead of 760 MB and takes 240 instead of 250 us, although a 1 x 4 wave layout reads 9 fragments per 14 MFMAs.
-            // Which equal height: the launch takes about (rounds of workgroups) x (time of one tile), a tile of h row blocks
-            // about (h + 4) units (measured at K = 3584: 49, 56, 62, 70, 82, 89 us for h = 3 .. 8), and a last round counts
-            // in full unless it is nearly empty (measured on 148 column tiles: 296 and 444 workgroups on 256 CUs take the
-            // same time).  E.g. 384 rows: three tiles of 128 (444 workgroups, 112 us) instead of two of 192 (296, 139 us);
-            // 448 rows: three of 160 (124 against 151 us); 896 rows: five of 192 (218 against 232 us).
-            const int mb = (M + 31) / 32, tn = (N + 255) / 256, cus = cu_count();
-            int hb = 8;
-            double best = 1e30;
-            for (int h = 8; h >= 3; --h) {
-                const double x = (double)((mb + h - 1) / h) * tn / cus, whole = (double)(long)x, frac = x - whole;
-                const double rounds = frac <= 0 ? whole : x <= 2.0 ? whole + 1 : whole + (frac > 0.4 ? 1.0 : 0.6 + frac);
-                const double cost = rounds * (h + 4);
-                if (cost < best * 0.999) { best = cost; hb = h; }
-            }
+            // The height comes from pick_tile_height: e.g. 384 rows run as three tiles of 128 (444 workgroups, 112 us)
+            // instead of two of 192 (296 workgroups, 139 us), 448 rows as three of 160 (124 against 151 us), 896 rows as
+            // five of 192 (218 against 232 us).
+            const int hb = pick_tile_height(M, N, 3);
             if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
             else if (hb == 5) launch_one<1, 4, 5, 2, 5, EPI_SILU_FRAG, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
@@ -771,7 +780,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         else gemm_reduce_kernel<EPI_F32_ROWMAJOR><<<g, 256, 0, st>>>(w4, slices, group, mn4, C);
         return false;
     }
-    if (M <= 512) {      // few rows, enough tiles (QKV at a few hundred rows): 128x64 tiles, slices folded in registers
+    if (M <= 512 && ((M + 127) / 128) * ((N + 63) / 64) <= cu_count()) {      // few rows, enough tiles for one round of them (QKV at a few hundred rows): 128x64 tiles, slices folded in registers
         switch (epi) {
         case EPI_BF16_ROWMAJOR: launch_one<2, 2, 2, 1, 5, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
         case EPI_RESID_F32: launch_one<2, 2, 2, 1, 5, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
