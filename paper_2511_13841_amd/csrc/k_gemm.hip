@@ -664,7 +664,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         // ... and at 257..512 rows on 4 waves of 128x64 or 96x64 (128x256 or 96x256 tiles), whichever pads M less:
         // 221 -> 186 us for the 1.5B head at 320 rows against 256x256 tiles of 8 waves
         const bool rows96 = (M + 95) / 96 * 96 < (M + 127) / 128 * 128;
-        if (epi == EPI_ROWMAX && (M > 512 || pad288 >= pad256)) {      // (up to 288 rows: one 288-row tile, below)
+        if (epi == EPI_ROWMAX) {
             // M tiles of equal height, as for gate/up at many rows below: e.g. 448 rows are two tiles of 224, not five of 96
             const int hb = pick_tile_height(M, N, 3);
             if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
@@ -710,6 +710,20 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         return false;
     }
     if (N >= 16384) {      // wide output, up to 256 rows (LM head of a small batch): one pass over K like every wide GEMM
+        if (epi == EPI_ROWMAX) {
+            // 129 .. 256 rows: one M tile of 5 .. 8 row blocks per 256 columns (every weight tile is copied into LDS once)
+            // instead of two tiles of 128x64
+            const int hb = (M + 31) / 32;
+            if (hb == 1) launch_one<1, 4, 1, 2, 8, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 2) launch_one<1, 4, 2, 2, 7, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 3) launch_one<1, 4, 3, 2, 7, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 4) launch_one<1, 4, 4, 2, 6, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 5) launch_one<1, 4, 5, 2, 5, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            else launch_one<2, 2, 4, 4, 4, EPI_ROWMAX, 2, true, 0, true>(A, W, C, M, N, K, ldc, st);
+            return false;
+        }
         launch_cfg3<2, 2, 2, 1, 5>(epi, A, W, C, M, N, K, ldc, st);
         return false;
     }

@@ -48,7 +48,8 @@ def test_gate_up_silu_epilogue_against_fp64(das, M, F, K):
     np.testing.assert_allclose(got, ref, rtol=2.0 ** -8, atol=1e-5 * np.sqrt(K) * np.abs(ref).max())
 
 
-@pytest.mark.parametrize("M,N,K", [(5, 16384, 128), (272, 16512, 128), (470, 16512, 128), (300, 16640, 192), (530, 16400, 128), (1088, 16384, 256)])
+@pytest.mark.parametrize("M,N,K", [(5, 16384, 128), (40, 16384, 128), (70, 16400, 128), (100, 16384, 128), (130, 16512, 128), (170, 16384, 128),
+                                   (200, 16384, 128), (250, 16512, 128), (272, 16512, 128), (470, 16512, 128), (300, 16640, 192), (530, 16400, 128), (1088, 16384, 256)])
 def test_row_maximum_epilogue_against_fp64(das, M, N, K):
     """The LM-head GEMM of a greedy pass keeps only the lowest column of each row's maximum: equal to the argmax of
     the fp64 product wherever its top two values are further apart than the fp32 accumulation error; planted ties
