@@ -214,6 +214,17 @@ int das_debug_gemm_time(int32_t epi, int32_t M, int32_t N, int32_t K, int32_t it
 int das_debug_copy_ring(int32_t workgroups, int32_t stages, int32_t copies, int32_t shared_copies, int32_t tiles,
                         int32_t non_temporal, double *us, double *bytes_into_lds);
 
+/* The matrix pipe by itself: 256 workgroups of 4 waves (one wave per SIMD, one workgroup per compute unit) each run
+ * `iters` iterations of two k-steps of 16 independent v_mfma_f32_32x32x16_bf16, the inner loop of the 256x256-tile GEMM.
+ * mode 0: operands constant, in registers; 1: every k-step's eight operand fragments read from LDS (pseudo-random bf16
+ * bit patterns), requested one k-step ahead; 2: as 1 plus that GEMM's copy traffic (8 KiB per wave and k-tile from an
+ * L2-resident region into a four-stage LDS ring, s_waitcnt + s_barrier per k-tile).  *ns_per_mfma = loop time of one
+ * wave / its MFMAs (constant 100 MHz counter), *shader_ghz = shader-clock cycles of that loop / its time (the clock the
+ * loop ran at: the chip lowers it under matrix load), *pflops = the launch's bf16 rate over its HIP-event duration.
+ * This is the ceiling the GEMM kernels' MFMA fractions are read against.  Allocates and frees its buffers; needs no
+ * model; iters <= 100000, anything else is DAS_ERR_INVALID. */
+int das_debug_mfma_loop(int32_t mode, int32_t iters, double *ns_per_mfma, double *shader_ghz, double *pflops);
+
 /* Device-to-device copy of `bytes` (multiple of 16) by a trivial kernel, `repeats` times: a dispatch of
  * known HBM traffic (bytes read + bytes written) against which profiler byte counters are scaled. */
 int das_debug_copy(int64_t bytes, int32_t repeats);

@@ -71,6 +71,7 @@ def lib():
             "das_gemm_noalloc": [I, I, I, VP, VP, VP, VP],
             "das_debug_copy": [C.c_int64, I],
             "das_debug_copy_ring": [I, I, I, I, I, I, C.POINTER(C.c_double), C.POINTER(C.c_double)],
+            "das_debug_mfma_loop": [I, I, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)],
             "das_profile_enable": [P, I],
             "das_profile_reset": [P],
             "das_profile_read": [P, I, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
@@ -171,6 +172,14 @@ def debug_copy_ring(workgroups, stages, copies, shared_copies, tiles=256, non_te
     _chk(lib().das_debug_copy_ring(int(workgroups), int(stages), int(copies), int(shared_copies), int(tiles), int(bool(non_temporal)),
                                    C.byref(us), C.byref(nb)), "das_debug_copy_ring")
     return us.value, nb.value
+
+
+def debug_mfma_loop(mode, iters=4000):
+    """The matrix pipe by itself (mode 0 register operands, 1 operands from LDS, 2 with the GEMM's copy traffic):
+    (ns per MFMA and SIMD, shader clock in GHz, PFLOP/s of the launch)."""
+    ns, ghz, pf = C.c_double(), C.c_double(), C.c_double()
+    _chk(lib().das_debug_mfma_loop(int(mode), int(iters), C.byref(ns), C.byref(ghz), C.byref(pf)), "das_debug_mfma_loop")
+    return ns.value, ghz.value, pf.value
 
 
 def debug_copy(nbytes, repeats=1):

@@ -1193,6 +1193,44 @@ extern "C" int das_debug_copy_ring(int32_t workgroups, int32_t stages, int32_t c
     return rc;
 }
 
+
+// The matrix-pipe probe of k_probe.hip: best of three launches after a warm-up.
+extern "C" int das_debug_mfma_loop(int32_t mode, int32_t iters, double *ns_per_mfma, double *shader_ghz, double *pflops) {
+    if (mode < 0 || mode > 2 || iters < 1 || iters > 100000 || !ns_per_mfma || !shader_ghz || !pflops) return DAS_ERR_INVALID;
+    const size_t src_bytes = (size_t)256 * 128 * 1024;
+    void *src = nullptr, *aux = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = DAS_OK;
+    auto bad = [&](hipError_t e) { if (e != hipSuccess) { g_dev_err = hipGetErrorString(e); rc = DAS_ERR_DEVICE; } return e != hipSuccess; };
+    do {
+        if (bad(hipMalloc(&src, src_bytes)) || bad(hipMalloc(&aux, 256)) || bad(hipMemset(src, 1, src_bytes)) || bad(hipMemset(aux, 0, 256)) ||
+            bad(hipEventCreate(&e0)) || bad(hipEventCreate(&e1)) || bad(hipDeviceSynchronize())) break;
+        float *sink = reinterpret_cast<float *>(aux);
+        long long *clk = reinterpret_cast<long long *>(reinterpret_cast<unsigned char *>(aux) + 64);
+        float best = 0.f;
+        long long best_clk[2] = {0, 0};
+        for (int r = 0; r < 4 && rc == DAS_OK; ++r) {
+            if (bad(hipEventRecord(e0, nullptr)) || bad(launch_mfma_loop(mode, src, sink, iters, clk, nullptr)) ||
+                bad(hipEventRecord(e1, nullptr)) || bad(hipEventSynchronize(e1))) break;
+            float ms = 0.f;
+            long long c[2];
+            if (bad(hipEventElapsedTime(&ms, e0, e1)) || bad(hipMemcpy(c, clk, sizeof c, hipMemcpyDeviceToHost))) break;
+            if (r >= 1 && (best == 0.f || ms < best)) { best = ms; best_clk[0] = c[0]; best_clk[1] = c[1]; }
+        }
+        if (rc != DAS_OK) break;
+        const double mfmas_per_wave = (double)iters * 32.0;                       // 2 k-steps x 16 per iteration
+        const double loop_ns = (double)best_clk[1] * 10.0;                        // 100 MHz ticks
+        *ns_per_mfma = loop_ns / mfmas_per_wave;
+        *shader_ghz = loop_ns > 0 ? (double)best_clk[0] / loop_ns : 0.0;
+        // 256 CUs x 4 SIMDs, 32 x 32 x 16 x 2 flop per MFMA, over the launch's own duration (events)
+        *pflops = 256.0 * 4.0 * mfmas_per_wave * 32768.0 / ((double)best * 1e-3) / 1e15;
+    } while (0);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(src); (void)hipFree(aux);
+    return rc;
+}
+
 // ------------------------------------------------------------------------------------------------ profiling / errors
 
 extern "C" int das_profile_enable(das_model *m, int32_t on) {

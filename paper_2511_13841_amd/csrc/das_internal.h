@@ -122,6 +122,8 @@ bool gemm_rowstats_supported(int M, int N);
 bool copy_ring_supported(int stages, int copies, int shared_copies);
 hipError_t launch_copy_ring(const void *priv, const void *shared_r, int workgroups, int stages, int copies, int shared_copies,
                             int tiles, bool non_temporal, hipStream_t st);
+// matrix-pipe probe (k_probe.hip): mode 0 register operands, 1 operands from LDS, 2 with the GEMM's copy traffic
+hipError_t launch_mfma_loop(int mode, const void *src, float *sink, int iters, long long *clk, hipStream_t st);
 void gemm_debug_copies_only(bool on);      // timing mode of das_debug_gemm_time: launches copy their tiles and multiply nothing
 int gemm_slices(int K, int *slice_tiles);
 int gemm_slice_group(int slices);                       // eight slices are added as two groups of four (0: one ascending run)

@@ -68,6 +68,72 @@ hipError_t launch_ring(const uint4 *priv, const uint4 *shared_r, int workgroups,
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------------
+// Matrix-pipe probe: what a loop of v_mfma_f32_32x32x16_bf16 delivers, and at which shader clock.
+//
+// 256 workgroups of 4 waves (one per SIMD; more than half of a CU's LDS each, so one workgroup per CU), every wave issuing
+// 16 independent MFMAs per k-step, as a wave of the 256x256-tile GEMM does.  MODE 0: operands constant, in registers.
+// MODE 1: the 8 operand fragments of every k-step are read from LDS (pseudo-random bf16 bit patterns) one k-step ahead,
+// requests dealt out one per MFMA as in the GEMM's pipelined loop.  MODE 2: as 1, plus the GEMM's copy traffic: per
+// k-tile of two k-steps every wave copies 8 KiB from an L2-resident region into a four-stage LDS ring, with the
+// s_waitcnt + s_barrier per k-tile of the real loop.  Thread 0 of one workgroup brackets the loop with the shader-clock
+// counter (s_memtime) and the constant 100 MHz counter (s_memrealtime): their ratio is the clock the loop ran at.
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+
+template <int MODE>
+__global__ __launch_bounds__(256) void mfma_loop_kernel(const uint4 *__restrict__ src, float *__restrict__ sink, int iters,
+                                                        long long *__restrict__ clk) {
+    extern __shared__ __align__(16) unsigned char smem[];      // 128 KiB: four stages of 32 KiB
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int i = tid; i < 32768; i += 256) {      // bf16 pairs with random sign and mantissa, exponents of 0.5 .. 2
+        uint32_t h = (uint32_t)i * 2654435761u; h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        reinterpret_cast<uint32_t *>(smem)[i] = (h & 0x807F807Fu) | 0x3F003F00u;
+    }
+    __syncthreads();
+    probe_bf16x8 fa[2][4], fb[2][4];
+    for (int p = 0; p < 2; ++p)
+        for (int q = 0; q < 4; ++q)
+            for (int i = 0; i < 8; ++i) { fa[p][q][i] = (__bf16)1.0f; fb[p][q][i] = (__bf16)1.0f; }
+    probe_f32x16 acc[16];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    const unsigned char *rb = smem + lane * 16 + (wave & 1) * 8192;
+    const uint4 *g = src + (size_t)blockIdx.x * 8192 + wave * 512 + lane;      // 128 KiB per workgroup, re-read every other k-tile
+    int stage = 0;
+    const long long t0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (MODE == 2 && ks == 1) {
+                __builtin_amdgcn_s_waitcnt(0xF70 | 8);      // all but the newest tile's copies have landed
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][m & 3], fa[ks][m >> 2], acc[m], 0, 0, 0);
+                if (MODE >= 1 && m < 4) fb[ks ^ 1][m] = *reinterpret_cast<const probe_bf16x8 *>(rb + stage * 32768 + 16384 + (ks * 4 + m) * 1024);
+                else if (MODE >= 1 && m < 8) fa[ks ^ 1][m - 4] = *reinterpret_cast<const probe_bf16x8 *>(rb + stage * 32768 + (ks * 4 + m - 4) * 1024);
+                else if (MODE == 2 && m >= 12)
+                    ring_copy(g + ((ks * 4 + m - 12) * 4 + (it & 1) * 32) * 64, base + ((stage + 3) & 3) * 32768 + wave * 8192 + (ks * 4 + m - 12) * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (MODE >= 1) stage = (stage + 1) & 3;
+    }
+    __builtin_amdgcn_s_waitcnt(0xF70);
+    const long long t1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+    if (blockIdx.x == 17 && tid == 0) { clk[0] = t1 - t0; clk[1] = r1 - r0; }
+    float s = 0.f;
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 1.2345f) sink[0] = s;      // keeps the accumulators alive
+}
+
 }  // namespace
 
 // the ring shapes that are built: stages, copies per wave and tile, of which shared
@@ -87,5 +153,21 @@ hipError_t launch_copy_ring(const void *priv, const void *shared_r, int workgrou
         return (non_temporal && nls < nl) ? launch_ring<ns, nl, nls, (nls < nl)>(p, s, workgroups, tiles, st) : launch_ring<ns, nl, nls, false>(p, s, workgroups, tiles, st);
     COPY_RING_SHAPES(RING)
 #undef RING
+    return hipErrorInvalidValue;
+}
+
+// src: at least 256 x 128 KiB of initialised device memory; clk: two 64-bit counters (shader cycles, 100 MHz ticks)
+hipError_t launch_mfma_loop(int mode, const void *src, float *sink, int iters, long long *clk, hipStream_t st) {
+    const uint4 *p = reinterpret_cast<const uint4 *>(src);
+    constexpr int LDS = 128 * 1024;
+    auto go = [&](auto kern) -> hipError_t {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        kern<<<dim3(256), dim3(256), LDS, st>>>(p, sink, iters, clk);
+        return hipGetLastError();
+    };
+    if (mode == 0) return go(mfma_loop_kernel<0>);
+    if (mode == 1) return go(mfma_loop_kernel<1>);
+    if (mode == 2) return go(mfma_loop_kernel<2>);
     return hipErrorInvalidValue;
 }

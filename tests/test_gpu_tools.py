@@ -55,3 +55,18 @@ def test_copy_ring_probe_shows_what_bounds_the_copy_streams():
     assert full < 0.6 * miss_nt
     with pytest.raises(das.DasError):
         das.debug_copy_ring(32, 7, 4, 0)         # unsupported ring shape
+
+
+def test_mfma_loop_probe_gives_the_ceiling_the_gemm_fractions_are_read_against():
+    """das_debug_mfma_loop, the matrix pipe by itself: a 32x32x16 bf16 MFMA occupies its SIMD for about 32 shader cycles in
+    every mode, the rate of the chip stays under the published 2.5 PFLOP/s, and the loop that reads random operands from
+    LDS runs at a lower shader clock -- and so a lower rate -- than the loop on constant registers (the chip holds its
+    power by lowering the clock): the GEMM kernels cannot beat the last mode's rate."""
+    import paper_2511_13841_amd as das
+    res = {m: das.debug_mfma_loop(m, 3000) for m in (0, 1, 2)}
+    for m, (ns, ghz, pf) in res.items():
+        print(f"mfma loop mode {m}: {ns:.2f} ns per MFMA, {ns * ghz:.1f} cycles, {ghz:.2f} GHz, {pf:.3f} PFLOP/s")
+        assert 0.8 < ghz < 2.6 and 28.0 < ns * ghz < 48.0 and 0.5 < pf < 2.5
+    assert res[1][2] < res[0][2] * 1.02 and res[2][2] < res[0][2] * 1.02
+    with pytest.raises(das.DasError):
+        das.debug_mfma_loop(3)
