@@ -809,6 +809,17 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     const int tn = (N + 127) / 128;
     const long cost128 = (long)((((M + 127) / 128) * tn + n_cu - 1) / n_cu) * 128;
     const long cost192 = (long)((((M + 191) / 192) * tn + n_cu - 1) / n_cu) * 192;
+    // 256x128 tiles (8 waves of 64x64) when they fit one round and both smaller shapes need two: one tile of 256 rows copies
+    // a quarter less than two of 128 (QKV at 1475 rows: 216 tiles instead of 432).  Slices in one ascending run only (the
+    // grouped sum of a long K needs the third accumulator set, which this shape has no registers for).
+    if (group == 0 && ((M + 255) / 256) * tn <= n_cu && cost128 > 128 && cost192 > 192) {
+        switch (epi) {
+        case EPI_BF16_ROWMAJOR: launch_one<4, 2, 2, 2, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        case EPI_RESID_F32: launch_one<4, 2, 2, 2, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        default: launch_one<4, 2, 2, 2, 3, EPI_F32_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
+        }
+        return false;
+    }
     if (cost192 < cost128) {
         switch (epi) {
         case EPI_BF16_ROWMAJOR: launch_one<3, 4, 2, 1, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;

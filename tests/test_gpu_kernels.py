@@ -76,12 +76,12 @@ def test_row_maximum_epilogue_against_fp64(das, M, N, K):
 
 
 @pytest.mark.parametrize("N,K,rows", [(320, 3584, 600), (192, 18944, 600), (16416, 1024, 600), (256, 960, 600), (2048, 16384, 600),
-                                      (400, 16384, 1100), (2048, 16384, 2250), (2048, 16384, 3000)])
+                                      (400, 16384, 1100), (2048, 16384, 2250), (2048, 16384, 3000), (4608, 3584, 1475)])
 def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K, rows):
     """A row of the product is the same bits whether it is computed among 7, 70, 300, 600 or 2250 rows: narrow outputs
     sum K in slices whose layout and grouping depend on K alone, whichever kernel shape the row count selects (slices
     over workgroups, folded in registers, the two slice groups of a long K in two workgroups on 192- or 256-row tiles,
-    or -- too many tiles for one round, 3000 rows -- grouped inside one workgroup); wide outputs sum K in one pass at every row count."""
+    or -- too many tiles for one round, 3000 rows -- grouped inside one workgroup; 256x128 tiles where those alone fit one round, 1475 rows x 4608 columns); wide outputs sum K in one pass at every row count."""
     rng = np.random.default_rng(N + K)
     a = di.f32_to_bf16(rng.standard_normal((rows, K)).astype(np.float32))
     w = di.f32_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
