@@ -276,8 +276,12 @@ static int run_pass(das_model *m, const std::vector<PassBlock> &blocks, const fl
         if (!xn_ready) { ProfScope ps(m, KC_RMSNORM); launch_rmsnorm(m->h, w.g1, m->xn, nullptr, T, dm.d, dm.rms_eps, st); }
         // (few rows: the K-slice partials of QKV stay in the workspace and the rotation kernel adds them)
         int qkv_slices = 1;
-        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats, nullptr, &qkv_slices); }
-        { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, qkv_slices > 1 ? m->gemm_ws : m->qkv, qkv_slices, m->q_h, m->cs, kl, vl, dm, m->d_kv_sat, st); }
+        // (many rows, head dim 128: the GEMM's epilogue rotates and stores q, k, v itself and reports 0 slices left)
+        const RopeEpi re = {pm.row_b, pm.row_pos, pm.b_slot, pm.page_table, pm.max_pages, reinterpret_cast<const float2 *>(m->cs),
+                            m->q_h, kl, vl, dm.Hq, dm.Hkv, m->d_kv_sat};
+        { ProfScope ps(m, KC_GEMM_QKV); launch_gemm(EPI_F32_ROWMAJOR, m->xn, w.wqkv, m->qkv, T, dm.qkvN, dm.d, dm.qkvN, st, m->gemm_ws, m->gemm_ws_floats, nullptr, &qkv_slices,
+                                                    nullptr, 0.f, dm.D == 128 ? &re : nullptr); }
+        if (qkv_slices > 0) { ProfScope ps(m, KC_ROPE_KV); launch_rope_kv(pm, qkv_slices > 1 ? m->gemm_ws : m->qkv, qkv_slices, m->q_h, m->cs, kl, vl, dm, m->d_kv_sat, st); }
         {
             ProfScope ps(m, KC_ATTN);
             for (int c = 0; c < 3; ++c)

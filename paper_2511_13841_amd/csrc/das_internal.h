@@ -84,7 +84,45 @@ struct PassMeta {
 // row with atomic max (value in the high word as an order-preserving integer, ~column in the low word)
 // EPI_ROWSTATS: no matrix is written either; per row and 32-column block the softmax statistics (block maximum, sum of
 // exp((l - max) / T)) and, per row, the logit of one given column (the row's draft token): what a sampling pass needs
-enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3, EPI_ROWMAX = 4, EPI_ROWSTATS = 5 };
+// EPI_ROPE_KV: no matrix is written; the QKV projection's rows are rotated, rounded and stored as rope_kv_kernel would
+// (q to the binary16 query buffer, k and v into their pages), from the accumulators.  Tiles of exactly one head (128 columns).
+enum GemmEpilogue { EPI_BF16_ROWMAJOR = 0, EPI_RESID_F32 = 1, EPI_SILU_FRAG = 2, EPI_F32_ROWMAJOR = 3, EPI_ROWMAX = 4, EPI_ROWSTATS = 5, EPI_ROPE_KV = 6 };
+
+// What the rotation + KV-write step needs besides the projections: the pass's row tables, the angles, the outputs.
+struct RopeEpi {
+    const int *row_b, *row_pos, *b_slot, *page_table;
+    int max_pages;
+    const float2 *cs;              // [T][D/2] (cos, sin)
+    f16_t *q_h, *kpool, *vpool;    // rotated queries [T][Hq*D]; this layer's K and V pages
+    int Hq, Hkv;
+    unsigned long long *sat;       // count of K/V elements that did not fit their container
+};
+
+#ifdef __HIPCC__
+// ---- arithmetic shared by rope_kv_kernel and the GEMM epilogue that replaces it at many rows: one definition, so that a
+// row has the same bits whichever of the two wrote it.
+__device__ __forceinline__ float das_bf16_round(float f) {      // fp32 -> nearest-even bf16 -> fp32
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return __uint_as_float(u & 0xFFFF0000u);
+}
+// binary16 bit pattern of x, round to nearest even, saturating at the largest finite value
+__device__ __forceinline__ f16_t das_f2h(float x) {
+    const _Float16 h = (_Float16)fminf(fmaxf(x, -65504.f), 65504.f);
+    return __builtin_bit_cast(f16_t, h);
+}
+// a K or V element: rounded to bf16 exactly once (the cache precision), then kept in a binary16 container; counted in
+// *sat when the bf16 value does not fit the container (NaN counts too)
+__device__ __forceinline__ f16_t das_kv_elem_counted(float x, unsigned long long *sat) {
+    const float b = das_bf16_round(x);
+    if (!(fabsf(b) <= 65504.f)) atomicAdd(sat, 1ull);
+    return das_f2h(b);
+}
+// rotate-half pair (x1 at dim i, x2 at dim i + D/2) by the angle (c.x, c.y) = (cos, sin): one multiply and one fused
+// multiply-add each, written out so that every caller compiles to the same two instructions
+__device__ __forceinline__ float das_rope_first(float x1, float x2, float2 c) { return __builtin_fmaf(x1, c.x, -(x2 * c.y)); }
+__device__ __forceinline__ float das_rope_second(float x1, float x2, float2 c) { return __builtin_fmaf(x2, c.x, x1 * c.y); }
+#endif
 
 // ---- launchers (each enqueues on `st`; none synchronises) ----
 void launch_pack_weight(const bf16_t *src, bf16_t *dst, int N, int K, int Np, int Kp, hipStream_t st);
@@ -112,11 +150,13 @@ void launch_rope_kv(const PassMeta &pm, const float *qkv, int slices, f16_t *q_h
 // left_slices (EPI_F32_ROWMAJOR only): a caller whose next kernel can add the K-slice partials itself passes a pointer.
 // When the launch leaves the partials in ws ([slices][M][N], to be added in ascending order) it stores their count there
 // and C stays unwritten; otherwise it stores 1 and C holds the product.
+// rope (EPI_F32_ROWMAJOR with left_slices only, head dim 128): when the launch shape allows it the rotation + KV write is
+// done from the accumulators (EPI_ROPE_KV); the launch then stores 0 in *left_slices and C stays unwritten.
 // EPI_ROWSTATS (only where gemm_rowstats_supported): C = float2 [ceil(N/32)][ldc] block statistics followed by float [ldc]
 // draft logits; aux_tok[row] = the column whose logit is wanted (-1: none), aux_f = 1 / temperature.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
                  float *ws, size_t ws_floats, const GemmNormTail *tail = nullptr, int *left_slices = nullptr,
-                 const int *aux_tok = nullptr, float aux_f = 0.f);
+                 const int *aux_tok = nullptr, float aux_f = 0.f, const RopeEpi *rope = nullptr);
 bool gemm_rowstats_supported(int M, int N);
 // copy-ring probe (k_probe.hip): stages x (4 * copies) KiB ring, 4 waves; the built shapes are listed there
 bool copy_ring_supported(int stages, int copies, int shared_copies);

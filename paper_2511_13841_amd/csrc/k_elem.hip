@@ -218,24 +218,15 @@ void launch_rope_table(const PassMeta &pm, const double *inv_freq, float *cs, in
 }
 
 // ---------------------------------------------------------------- RoPE on q and k; K/V rows -> pages
-// binary16 bit pattern of x, round to nearest even, saturating at the largest finite value
-__device__ __forceinline__ f16_t f2h(float x) {
-    const _Float16 h = (_Float16)fminf(fmaxf(x, -65504.f), 65504.f);
-    return __builtin_bit_cast(f16_t, h);
-}
+__device__ __forceinline__ f16_t f2h(float x) { return das_f2h(x); }
 __device__ __forceinline__ float h2f(f16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
 // a K or V element: rounded to bf16 exactly once (the cache precision), then kept in a binary16 container, which is
 // exact for every bf16 value with 2^-17 <= |x| <= 65504 (smaller ones move by at most 3e-8, larger ones saturate).
 // The attention kernel's matrix instructions are the f16 ones: next to these values the rotated query and the
 // probabilities then carry 11 significant bits in one term.
 __device__ __forceinline__ f16_t kv_elem(float x) { return f2h(bf2f(f2bf(x))); }
-// the same store, counted in *sat when the bf16 value does not fit the container (NaN counts too): the cache then no
-// longer holds what was computed, and the caller can see it (das_debug_kv_saturated)
-__device__ __forceinline__ f16_t kv_elem_counted(float x, unsigned long long *sat) {
-    const float b = bf2f(f2bf(x));
-    if (!(fabsf(b) <= 65504.f)) atomicAdd(sat, 1ull);
-    return f2h(b);
-}
+// the same store, counted in *sat when the bf16 value does not fit the container (das_debug_kv_saturated)
+__device__ __forceinline__ f16_t kv_elem_counted(float x, unsigned long long *sat) { return das_kv_elem_counted(x, sat); }
 
 // grid (T, heads / heads per workgroup), block 256 = 256 / (D/2) heads: thread i of a head owns the rotate-half pair
 // (i, i + D/2).  The projections arrive in fp32 and are rounded exactly once, after the rotation: q to binary16, k and
@@ -250,7 +241,7 @@ __global__ void rope_kv_kernel(PassMeta pm, const float *__restrict__ qkv, int s
     for (int s = 1; s < slices; ++s) { x1 += row[s * slab + i]; x2 += row[s * slab + i + half]; }      // K-slice partials, in order
     if (hh < Hq + Hkv) {
         float2 c = cs[r * half + i];
-        float y1 = x1 * c.x - x2 * c.y, y2 = x2 * c.x + x1 * c.y;
+        float y1 = das_rope_first(x1, x2, c), y2 = das_rope_second(x1, x2, c);
         x1 = y1; x2 = y2;
     }
     if (hh < Hq) {

@@ -51,7 +51,7 @@ template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SP
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                              void *__restrict__ Cv, int M, int N, int K, int ldc,
                                                              int tiles_m, int tiles_n, int slice_tiles, int xslices,
-                                                             const int *__restrict__ aux_tok, float aux_f, int copies_only) {
+                                                             const int *__restrict__ aux_tok, float aux_f, int copies_only, RopeEpi re) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int AB = WGM * TM, BB = WGN * TN;          // 32-row blocks per tile
     constexpr int RBU = KS * 64;                          // 16-byte units of one row block in one k-tile
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
     constexpr bool PADDED = (UNITS % NT) != 0;           // s_waitcnt fits all; surplus copies go to a dump area
     static_assert((NS - 2) * NLOAD <= 63, "vmcnt is a 6-bit counter");
     static_assert(EPI != EPI_SILU_FRAG || TN % 2 == 0, "gate and up blocks must sit in the same wave");
-    constexpr bool TRANSPOSED = EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX || EPI == EPI_ROWSTATS;      // blocks with rows = weight rows
+    constexpr bool TRANSPOSED = EPI == EPI_SILU_FRAG || EPI == EPI_ROWMAX || EPI == EPI_ROWSTATS || EPI == EPI_ROPE_KV;      // blocks with rows = weight rows
     constexpr int STAGE_BYTES = (AB + BB) * KS * 1024;
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -451,6 +451,73 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(const bf16_t *__res
                 __builtin_amdgcn_sched_barrier(0);      // one block at a time: interleaved, the blocks' temporaries spill
             }
         }
+    } else if (EPI == EPI_ROPE_KV) {
+        // The tile is exactly one head of the QKV projection (128 columns = head dim): rotate, round and store what
+        // rope_kv_kernel would, from the accumulators.  Transposed blocks: a lane holds ONE row and, per block, four runs
+        // of four consecutive head dims, so q and k leave in 8-byte stores and the row's tables are looked up once.  The
+        // rotate-half partner of a dim (64 further on or back) sits in the same lane and register of another wave of the
+        // same wave row: the finished accumulators change hands through the LDS ring, which is free once every wave has
+        // left the k loop.
+        static_assert(EPI != EPI_ROPE_KV || (BB == 4 && (TN == 1 || TN == 2) && !CAN_COLSPLIT), "one head per tile");
+        static_assert(EPI != EPI_ROPE_KV || (size_t)NT * TM * TN * 16 * 4 <= (size_t)NS * STAGE_BYTES, "exchange area within the ring");
+        constexpr int PER_WAVE = TM * TN * 16 * 64;
+        float *xch = reinterpret_cast<float *>(smem);
+        __syncthreads();      // (every copy has landed: vmcnt(0) above)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[wave * PER_WAVE + ((i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+        __syncthreads();
+        const int hh = tile_n;                                                  // head: q heads, then k heads, then v heads
+        const int pwave = wm * WGN + (TN == 1 ? (wn ^ 2) : (wn ^ 1));
+        const bool rotate = hh < re.Hq + re.Hkv;
+        constexpr int D = 128, HALF = 64;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + i * 32 + lr;
+            if (row >= M) continue;
+            f16_t *dst = nullptr;       // q row, or the (page, head) block of k or v
+            int t = 0;
+            if (hh < re.Hq) dst = re.q_h + (size_t)row * re.Hq * D + (size_t)hh * D;
+            else {
+                const int b = re.row_b[row], pos = re.row_pos[row];
+                const int page = re.page_table[(size_t)re.b_slot[b] * re.max_pages + (pos >> 4)];
+                t = pos & 15;
+                dst = hh < re.Hq + re.Hkv ? re.kpool + ((size_t)page * re.Hkv + (hh - re.Hq)) * (size_t)(DAS_PAGE * D)
+                                          : re.vpool + ((size_t)page * re.Hkv + (hh - re.Hq - re.Hkv)) * (size_t)(DAS_PAGE * D);
+            }
+            const float4 *csrow = reinterpret_cast<const float4 *>(re.cs + (size_t)row * HALF);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c0 = (wn * TN + j) * 32 + 8 * q + 4 * lh;         // four consecutive head dims c0 .. c0 + 3
+                    float y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * q + e];
+                    if (rotate) {
+                        const float4 cs01 = csrow[(c0 & (HALF - 1)) >> 1], cs23 = csrow[((c0 & (HALF - 1)) >> 1) + 1];
+                        const float2 c[4] = {make_float2(cs01.x, cs01.y), make_float2(cs01.z, cs01.w), make_float2(cs23.x, cs23.y), make_float2(cs23.z, cs23.w)};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float other = xch[pwave * PER_WAVE + ((i * TN + j) * 16 + 4 * q + e) * 64 + lane];
+                            y[e] = c0 < HALF ? das_rope_first(y[e], other, c[e]) : das_rope_second(other, y[e], c[e]);
+                        }
+                    }
+                    if (hh < re.Hq) {
+                        const f16_t o[4] = {das_f2h(y[0]), das_f2h(y[1]), das_f2h(y[2]), das_f2h(y[3])};
+                        *reinterpret_cast<uint2 *>(dst + c0) = *reinterpret_cast<const uint2 *>(o);
+                    } else if (hh < re.Hq + re.Hkv) {
+                        const f16_t o[4] = {das_kv_elem_counted(y[0], re.sat), das_kv_elem_counted(y[1], re.sat), das_kv_elem_counted(y[2], re.sat), das_kv_elem_counted(y[3], re.sat)};
+                        *reinterpret_cast<uint2 *>(dst + kpage_off(t, c0)) = *reinterpret_cast<const uint2 *>(o);      // (dims c0 .. c0 + 3 are contiguous in a K page)
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) dst[vpage_off(t, c0 + e)] = das_kv_elem_counted(y[e], re.sat);
+                    }
+                }
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -478,7 +545,7 @@ void gemm_debug_copies_only(bool on) { g_copies_only = on; }
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI, int KS = 4, bool SPREAD = (NS >= 3), int SL = 0, bool PIPE = false, bool WNT = false>
 static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
                        int slice_tiles = 0, int slices = 1, bool slice_per_xcd = false, const int *aux_tok = nullptr, float aux_f = 0.f,
-                       int group = 0) {
+                       int group = 0, const RopeEpi *rope = nullptr) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int LDS = NS * (WGM * TM + WGN * TN) * KS * 1024 + WGM * WGN * 1024;      // ring + dump area for padded copies
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
@@ -489,14 +556,15 @@ static void launch_one(const bf16_t *A, const bf16_t *W, void *C, int M, int N, 
         configured = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const RopeEpi re = rope ? *rope : RopeEpi{};
     if (SL == 2 && slice_per_xcd && slices >= 2 && (8 % slices) == 0) {
         const int grid = ((tiles_m * tiles_n * slices + 7) / 8) * 8;
-        kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, slices, aux_tok, aux_f, (int)g_copies_only);
+        kern<<<dim3(grid), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, slices, aux_tok, aux_f, (int)g_copies_only, re);
         return;
     }
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
     // mode 2: one workgroup per slice; mode 3: `slices` groups of `group` slices; mode 1: `group` = slices of the first group (0: one run)
-    kern<<<dim3(grid, SL >= 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, group, aux_tok, aux_f, (int)g_copies_only);
+    kern<<<dim3(grid, SL >= 2 ? slices : 1), dim3(WGM * WGN * 64), LDS, st>>>(A, W, C, M, N, K, ldc, tiles_m, tiles_n, slice_tiles, group, aux_tok, aux_f, (int)g_copies_only, re);
 }
 
 // Sum of the slice partials in ascending order (in two groups when group > 0: slices [0, group) and [group, slices), each
@@ -611,7 +679,7 @@ static int pick_tile_height(int M, int N, int lo) {
 // EPI_ROWMAX needs N >= 16384 (the wide, one-pass shapes) and C = one zeroed 64-bit key per row.
 // For EPI_SILU_FRAG, N counts packed (gate+up interleaved) rows and ldc is the padded FFN width.
 bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int N, int K, int ldc, hipStream_t st,
-                 float *ws, size_t ws_floats, const GemmNormTail *tail, int *left_slices, const int *aux_tok, float aux_f) {
+                 float *ws, size_t ws_floats, const GemmNormTail *tail, int *left_slices, const int *aux_tok, float aux_f, const RopeEpi *rope) {
     if (left_slices) *left_slices = 1;
     if (M <= 0) return false;
     if (epi == EPI_ROWSTATS) {
@@ -812,7 +880,12 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     // 256x128 tiles (8 waves of 64x64) when they fit one round and both smaller shapes need two: one tile of 256 rows copies
     // a quarter less than two of 128 (QKV at 1475 rows: 216 tiles instead of 432).  Slices in one ascending run only (the
     // grouped sum of a long K needs the third accumulator set, which this shape has no registers for).
+    // QKV of a pass with many rows, head dim 128: every tile of these shapes is one head, so the rotation and the KV write
+    // are done from the accumulators (EPI_ROPE_KV) and the fp32 projections never go through memory
+    const bool fuse_rope = rope && left_slices && epi == EPI_F32_ROWMAJOR && group == 0 && (N % 128) == 0;
+    if (fuse_rope) *left_slices = 0;
     if (group == 0 && ((M + 255) / 256) * tn <= n_cu && cost128 > 128 && cost192 > 192) {
+        if (fuse_rope) { launch_one<4, 2, 2, 2, 3, EPI_ROPE_KV, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group, rope); return false; }
         switch (epi) {
         case EPI_BF16_ROWMAJOR: launch_one<4, 2, 2, 2, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
         case EPI_RESID_F32: launch_one<4, 2, 2, 2, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
@@ -821,6 +894,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         return false;
     }
     if (cost192 < cost128) {
+        if (fuse_rope) { launch_one<3, 4, 2, 1, 3, EPI_ROPE_KV, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group, rope); return false; }
         switch (epi) {
         case EPI_BF16_ROWMAJOR: launch_one<3, 4, 2, 1, 3, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
         case EPI_RESID_F32: launch_one<3, 4, 2, 1, 3, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
@@ -828,6 +902,7 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
         }
         return false;
     }
+    if (fuse_rope) { launch_one<2, 4, 2, 1, 4, EPI_ROPE_KV, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group, rope); return false; }
     switch (epi) {
     case EPI_BF16_ROWMAJOR: launch_one<2, 4, 2, 1, 4, EPI_BF16_ROWMAJOR, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
     case EPI_RESID_F32: launch_one<2, 4, 2, 1, 4, EPI_RESID_F32, 4, true, 1>(A, W, C, M, N, K, ldc, st, slice_tiles, slices, false, nullptr, 0.f, group); break;
