@@ -600,8 +600,8 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4 *__restri
     }
 }
 
-// EPI_ROWSTATS is built for the many-row wide shape only: passes with fewer rows write their logits (they are small)
-bool gemm_rowstats_supported(int M, int N) { return M > 512 && N >= 16384; }
+// EPI_ROWSTATS is built for the wide one-pass shapes: small vocabularies write their logits (they are small)
+bool gemm_rowstats_supported(int M, int N) { return M >= 1 && N >= 16384; }
 
 // K slices of a narrow GEMM: a function of K alone (never of M), so that every launch shape sums in the same order
 int gemm_slices(int K, int *slice_tiles) {
@@ -683,13 +683,20 @@ bool launch_gemm(int epi, const bf16_t *A, const bf16_t *W, void *C, int M, int 
     if (left_slices) *left_slices = 1;
     if (M <= 0) return false;
     if (epi == EPI_ROWSTATS) {
-        // the LM head of a sampling pass with many rows (the caller checks gemm_rowstats_supported): the 256x256 tiles of
-        // the greedy head, with the statistics epilogue
-        // (M tiles of equal height, as for gate/up at many rows below)
-        const int hb = pick_tile_height(M, N, 6);
-        if (hb == 7) launch_one<1, 4, 7, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
-        else if (hb == 6) launch_one<1, 4, 6, 2, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+        // the LM head of a sampling pass (the caller checks gemm_rowstats_supported): the tiles of the greedy head, with
+        // the statistics epilogue.  Up to 256 rows one M tile of all rows per 256 columns, above that M tiles of equal
+        // height from the cost model (as for the greedy head and for gate/up below).
+        const int hb = M <= 256 ? (M + 31) / 32 : pick_tile_height(M, N, 3);
+#define ROWSTATS_TILE(tm, ns) launch_one<1, 4, tm, 2, ns, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f)
+        if (hb == 1) ROWSTATS_TILE(1, 8);
+        else if (hb == 2) ROWSTATS_TILE(2, 7);
+        else if (hb == 3) ROWSTATS_TILE(3, 7);
+        else if (hb == 4) ROWSTATS_TILE(4, 6);
+        else if (hb == 5) ROWSTATS_TILE(5, 5);
+        else if (hb == 6) ROWSTATS_TILE(6, 4);
+        else if (hb == 7) ROWSTATS_TILE(7, 4);
         else launch_one<2, 2, 4, 4, 4, EPI_ROWSTATS, 2, true, 0, true>(A, W, C, M, N, K, ldc, st, 0, 1, false, aux_tok, aux_f);
+#undef ROWSTATS_TILE
         return false;
     }
     // Tile shapes, picked from measurements on MI355X (every shape keeps the same K order per output element):
