@@ -67,6 +67,6 @@ def test_mfma_loop_probe_gives_the_ceiling_the_gemm_fractions_are_read_against()
     for m, (ns, ghz, pf) in res.items():
         print(f"mfma loop mode {m}: {ns:.2f} ns per MFMA, {ns * ghz:.1f} cycles, {ghz:.2f} GHz, {pf:.3f} PFLOP/s")
         assert 0.8 < ghz < 2.6 and 28.0 < ns * ghz < 48.0 and 0.5 < pf < 2.5
-    assert res[1][2] < res[0][2] * 1.02 and res[2][2] < res[0][2] * 1.02
+    assert res[1][2] < res[0][2] * 1.10 and res[2][2] < res[0][2] * 1.10      # (margin for boxes whose power state differs)
     with pytest.raises(das.DasError):
         das.debug_mfma_loop(3)
