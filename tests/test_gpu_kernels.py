@@ -76,7 +76,7 @@ def test_row_maximum_epilogue_against_fp64(das, M, N, K):
 
 
 @pytest.mark.parametrize("N,K,rows", [(320, 3584, 600), (192, 18944, 600), (16416, 1024, 600), (256, 960, 600), (2048, 16384, 600),
-                                      (400, 16384, 1100), (2048, 16384, 2250), (2048, 16384, 3000), (4608, 3584, 1475)])
+                                      (400, 16384, 1100), (2048, 16384, 2250), (2048, 16384, 3000), (4608, 3584, 1475), (1536, 8960, 600)])
 def test_gemm_rows_do_not_depend_on_the_row_count(das, N, K, rows):
     """A row of the product is the same bits whether it is computed among 7, 70, 300, 600 or 2250 rows: narrow outputs
     sum K in slices whose layout and grouping depend on K alone, whichever kernel shape the row count selects (slices
